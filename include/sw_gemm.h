@@ -1,0 +1,134 @@
+/*
+ * sw_gemm.h -- C ABI of the MI355X (gfx950) Strassen-Winograd fp64 matrix multiply.
+ *
+ * The library computes C = A*B (Algorithm 1: Require A, B n x n; Ensure C = A*B)
+ * by walking the 7-way recursion tree of the Strassen-Winograd step (Appendix A)
+ * with a caller-chosen or planned order of BFS steps (all seven subproblems in
+ * flight, Section 3.3) and DFS steps (subproblems in sequence, Section 3.4), and
+ * classical fp64 leaf products below the cutoff (Section 5.4.1).
+ *
+ * Conventions for every call
+ *   - matrices are fp64, row-major; pointers named A, B, C, T, S, Q, X, ... are
+ *     DEVICE pointers; `const char*`, `char*`, `int64_t*`, `double* ms` are HOST pointers;
+ *   - the caller owns every buffer, the library never allocates or frees device memory;
+ *   - work is enqueued on the stream given to sw_set_stream (default: the null
+ *     stream) without host synchronisation; results are valid after the caller
+ *     synchronises that stream;
+ *   - return value 0 = SW_OK, negative = error; sw_last_error() gives the text of
+ *     the calling thread's last failure.
+ *   - a schedule is a string of `levels` characters, 'B' (BFS step) or 'D' (DFS
+ *     step), top level of the tree first; NULL or "" asks the planner.
+ * Calls that share one workspace must not overlap in time.
+ */
+#ifndef SW_GEMM_H
+#define SW_GEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SW_OK 0
+#define SW_EINVAL (-1) /* bad argument: n < 0, levels < 0 or > SW_MAX_LEVELS, 2^levels > n, NULL pointer,
+                          schedule of wrong length or with a character other than B/D, C overlapping A or B */
+#define SW_ENOMEM (-2) /* workspace missing or smaller than sw_plan_memory says; no schedule fits the budget */
+#define SW_EHIP (-3)   /* a HIP call failed; text in sw_last_error() */
+
+#define SW_MAX_LEVELS 16
+
+/* ---- the product (Algorithm 1; Appendix A; Sections 3.3, 3.4) ------------------------------------------- */
+
+/* C = A*B, all n x n with leading dimension n.  `levels` Strassen-Winograd steps, then classical leaves of
+ * size ceil(n / 2^levels).  levels = 0 is one classical product.  If n is not a multiple of 2^levels the
+ * operands are zero-padded into workspace copies of the next multiple (Section 3.1 allows padding).
+ * A and B are read only; C is overwritten; C must not overlap A or B.  Uses the workspace and stream set by
+ * sw_set_workspace / sw_set_stream.  schedule NULL or "": the planner's choice for the current workspace
+ * size (sw_plan_schedule with budget = workspace bytes). */
+int sw_gemm(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule);
+
+/* Same with explicit leading dimensions, workspace and stream (no library state is read).
+ * workspace: DEVICE pointer, 256-byte aligned, workspace_bytes >= sw_plan_memory(n, levels, schedule). */
+int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+               int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* ---- the planner (Section 3.1: pick the step order that uses the memory there is; Sections 3.3.1, 3.4.1) - */
+
+/* Bytes of workspace sw_gemm needs beyond A, B, C for this n, depth and step order (what THIS library
+ * allocates from the workspace: 21 half-size buffers per parent at a BFS step, 2 at a DFS step, padded
+ * leading dimensions, plus padded copies of A, B, C when 2^levels does not divide n).  schedule NULL or "":
+ * the all-DFS order (the minimum).  Pure host arithmetic; needs no GPU.  Negative = error code. */
+int64_t sw_plan_memory(int64_t n, int levels, const char* schedule);
+
+/* Choose the step order for n and levels under a workspace budget: among the orders that fit, the one with
+ * the most leaves per batched launch (most BFS steps, placed as deep as possible), DFS steps first among
+ * ties (the Limited-Memory scheme of Section 3.4).  out: HOST buffer of levels + 1 chars.  SW_ENOMEM if not
+ * even the all-DFS order fits. */
+int sw_plan_schedule(int64_t n, int levels, int64_t budget_bytes, char* out);
+
+/* The paper's memory model for a step order, in words: sum over levels i = 0..levels of 3 * live_i * n_i^2
+ * (i = 0 is A, B, C; live multiplies by 7 at a BFS step).  Equals P * Mem_UM (Section 3.3.1) for all-BFS
+ * and P * Mem_LM (Section 3.4.1) for DFS-then-BFS.  n must be a multiple of 2^levels. */
+int64_t sw_model_words(int64_t n, int levels, const char* schedule);
+
+/* Number of DFS steps of the Limited-Memory scheme, l = max(0, ceil(log2(4 n / (P^(1/w0) sqrt(M))))),
+ * w0 = log2 7 (Section 3.4, the equation that sets l; valid when 3 n^2 / P <= M / 3).  M in words. */
+int sw_lm_dfs_steps(double n, double P, double M_words);
+
+/* Actual arithmetic of one product: 7^levels * (2 m^3 - m^2) + 15 * sum_i 7^i (n_i / 2)^2 with
+ * m = n / 2^levels, i.e. F(n) = c_s n^w0 - 5 n^2 of Appendix A.  n must be a multiple of 2^levels. */
+double sw_flop_count(int64_t n, int levels);
+
+/* ---- library state -------------------------------------------------------------------------------------- */
+
+int sw_set_workspace(void* dev_ptr, int64_t bytes); /* caller-owned; NULL/0 clears it                    */
+int sw_set_stream(void* hip_stream);                /* hipStream_t; NULL = the null stream               */
+const char* sw_last_error(void);                    /* HOST string, valid until the thread's next call  */
+
+/* ---- the steps of the path, one call each (used by sw_gemm; exported so each can be tested and timed) ---- */
+
+/* Pre-additions of one BFS step (Appendix A, first and second column).  side 0: from each of `live` parents
+ * P (n x n, h = n/2) write T0..T6 = A11, A12, A21+A22, T2-A11, A11-A21, A12-T3, A22.  side 1: S0..S6 = B11,
+ * B21, B12-B11, B22-S2, B22-B12, B22, S3-B21.  Parent p starts at parent + p*parent_stride; child j of
+ * parent p starts at child + (7p + j)*child_stride and has leading dimension child_ld >= h.  Strides and
+ * leading dimensions in elements.  One pass: each input element read once, each output written once. */
+int sw_pre_add(int side, const double* parent, int64_t parent_ld, int64_t parent_stride, int64_t live,
+               int64_t h, double* child, int64_t child_ld, int64_t child_stride, void* hip_stream);
+
+/* Post-additions of one BFS step (Appendix A, fourth column): U1 = Q0+Q3, U2 = U1+Q4, U3 = U1+Q2,
+ * C11 = Q0+Q1, C12 = U3+Q5, C21 = U2-Q6, C22 = U2+Q2, in this association, for `live` parents. */
+int sw_post_add(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, int64_t h,
+                double* parent, int64_t parent_ld, int64_t parent_stride, void* hip_stream);
+
+/* Classical leaf products (Section 5.4.1): C_b = A_b * B_b for b < batch, each m x m, fp64 MFMA
+ * (v_mfma_f64_16x16x4_f64), one launch for the whole batch.  Operand b starts at base + b*stride. */
+int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t stride_a,
+                 const double* B, int64_t ldb, int64_t stride_b, double* C, int64_t ldc, int64_t stride_c,
+                 void* hip_stream);
+
+/* Zero-padded copy (rows x cols of src into the top-left of a prows x pcols dst, rest zero) and its
+ * inverse crop are the same call: the region copied is min(rows, prows) x min(cols, pcols). */
+int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
+                double* dst, int64_t dst_ld, int64_t prows, int64_t pcols, void* hip_stream);
+
+/* ---- measurement ---------------------------------------------------------------------------------------- */
+
+/* Kernel classes for sw_profile_read. */
+#define SW_CLASS_PRE_ADD 0  /* BFS pre-additions                        */
+#define SW_CLASS_POST_ADD 1 /* BFS post-additions                       */
+#define SW_CLASS_LEAF 2     /* batched leaf GEMM                        */
+#define SW_CLASS_DFS_ADD 3  /* element-wise kernels of DFS steps        */
+#define SW_CLASS_PAD 4      /* pad / crop copies                        */
+#define SW_NUM_CLASSES 5
+
+/* on != 0: bracket every kernel launch of sw_gemm with HIP events on the launch stream (no host sync).
+ * sw_profile_read synchronises those events, adds up per class the elapsed milliseconds, the launches and
+ * the algorithmic bytes (add kernels: distinct elements read + written, times 8) or flops (leaf: 2 m^3 per
+ * product) into HOST arrays of SW_NUM_CLASSES entries, and clears the record. */
+int sw_profile_enable(int on);
+int sw_profile_read(double* ms, int64_t* launches, double* work);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SW_GEMM_H */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding of libsw_gemm.so: the same names as the C ABI (include/sw_gemm.h), argument
+marshalling only.  Tensors are torch CUDA (HIP) tensors used for their device memory; every step of the
+path runs in the library's kernels.  There is no CPU fallback: a missing library raises."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsw_gemm.so")
+
+SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
+SW_MAX_LEVELS = 16
+CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad")
+
+EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
+           "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_last_error", "sw_pre_add", "sw_post_add",
+           "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
+
+
+class SwError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"sw_gemm library error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libsw_gemm.so (built by __graft_entry__.build()); raise if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(LIB_PATH)
+    i64, vp, cp, ci, dbl = ctypes.c_int64, ctypes.c_void_p, ctypes.c_char_p, ctypes.c_int, ctypes.c_double
+    sig = {
+        "sw_gemm": (ci, [i64, vp, vp, vp, ci, cp]),
+        "sw_gemm_ex": (ci, [i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
+        "sw_plan_memory": (i64, [i64, ci, cp]),
+        "sw_plan_schedule": (ci, [i64, ci, i64, ctypes.c_char_p]),
+        "sw_model_words": (i64, [i64, ci, cp]),
+        "sw_lm_dfs_steps": (ci, [dbl, dbl, dbl]),
+        "sw_flop_count": (dbl, [i64, ci]),
+        "sw_set_workspace": (ci, [vp, i64]),
+        "sw_set_stream": (ci, [vp]),
+        "sw_last_error": (cp, []),
+        "sw_pre_add": (ci, [ci, vp, i64, i64, i64, i64, vp, i64, i64, vp]),
+        "sw_post_add": (ci, [vp, i64, i64, i64, i64, vp, i64, i64, vp]),
+        "sw_leaf_gemm": (ci, [i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp]),
+        "sw_pad_copy": (ci, [vp, i64, i64, i64, vp, i64, i64, i64, vp]),
+        "sw_profile_enable": (ci, [ci]),
+        "sw_profile_read": (ci, [ctypes.POINTER(dbl), ctypes.POINTER(i64), ctypes.POINTER(dbl)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc < 0:
+        raise SwError(int(rc), lib().sw_last_error().decode())
+    return rc
+
+
+def _sched(s):
+    return None if s is None else s.encode()
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t):
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _f64_cuda(t, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float64):
+        raise TypeError(f"{name} must be a float64 tensor on the GPU")
+
+
+# ---- host-only calls ----------------------------------------------------------------------------------------
+
+def sw_plan_memory(n, levels, schedule=None):
+    return _check(lib().sw_plan_memory(n, levels, _sched(schedule)))
+
+
+def sw_plan_schedule(n, levels, budget_bytes):
+    buf = ctypes.create_string_buffer(SW_MAX_LEVELS + 1)
+    _check(lib().sw_plan_schedule(n, levels, budget_bytes, buf))
+    return buf.value.decode()
+
+
+def sw_model_words(n, levels, schedule):
+    return _check(lib().sw_model_words(n, levels, _sched(schedule)))
+
+
+def sw_lm_dfs_steps(n, P, M_words):
+    return _check(lib().sw_lm_dfs_steps(float(n), float(P), float(M_words)))
+
+
+def sw_flop_count(n, levels):
+    v = lib().sw_flop_count(n, levels)
+    if v < 0:
+        raise SwError(SW_EINVAL, "n must be a multiple of 2^levels")
+    return v
+
+
+def sw_last_error():
+    return lib().sw_last_error().decode()
+
+
+# ---- device calls ----------------------------------------------------------------------------------------------
+
+def sw_set_workspace(ws):
+    """ws: a uint8/any CUDA tensor the caller keeps alive, or None to clear."""
+    if ws is None:
+        return _check(lib().sw_set_workspace(None, 0))
+    return _check(lib().sw_set_workspace(_ptr(ws), ws.numel() * ws.element_size()))
+
+
+def sw_set_stream(stream_handle):
+    return _check(lib().sw_set_stream(ctypes.c_void_p(stream_handle)))
+
+
+def sw_gemm(n, A, B, C, levels, schedule=None):
+    """C = A @ B through the library state set by sw_set_workspace / sw_set_stream."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+        if not t.is_contiguous() or tuple(t.shape) != (n, n):
+            raise ValueError(f"{name} must be a contiguous {n} x {n} tensor")
+    return _check(lib().sw_gemm(n, _ptr(A), _ptr(B), _ptr(C), levels, _sched(schedule)))
+
+
+def sw_gemm_ex(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, stream_handle=None):
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+    ws_ptr = None if workspace is None else _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = _stream(C) if stream_handle is None else ctypes.c_void_p(stream_handle)
+    return _check(lib().sw_gemm_ex(n, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, levels, _sched(schedule),
+                                   ws_ptr, ws_bytes, st))
+
+
+def sw_pre_add(side, parent, parent_ld, parent_stride, live, h, child, child_ld, child_stride):
+    return _check(lib().sw_pre_add(side, _ptr(parent), parent_ld, parent_stride, live, h, _ptr(child), child_ld,
+                                   child_stride, _stream(child)))
+
+
+def sw_post_add(Q, q_ld, q_stride, live, h, parent, parent_ld, parent_stride):
+    return _check(lib().sw_post_add(_ptr(Q), q_ld, q_stride, live, h, _ptr(parent), parent_ld, parent_stride,
+                                    _stream(parent)))
+
+
+def sw_leaf_gemm(m, batch, A, lda, stride_a, B, ldb, stride_b, C, ldc, stride_c):
+    return _check(lib().sw_leaf_gemm(m, batch, _ptr(A), lda, stride_a, _ptr(B), ldb, stride_b, _ptr(C), ldc,
+                                     stride_c, _stream(C)))
+
+
+def sw_pad_copy(src, src_ld, rows, cols, dst, dst_ld, prows, pcols):
+    return _check(lib().sw_pad_copy(_ptr(src), src_ld, rows, cols, _ptr(dst), dst_ld, prows, pcols, _stream(dst)))
+
+
+def sw_profile_enable(on):
+    return _check(lib().sw_profile_enable(1 if on else 0))
+
+
+def sw_profile_read():
+    """-> {class name: dict(ms=..., launches=..., work=...)}; work is bytes for add kernels, flops for leaf_gemm."""
+    n = len(CLASS_NAMES)
+    ms = (ctypes.c_double * n)()
+    launches = (ctypes.c_int64 * n)()
+    work = (ctypes.c_double * n)()
+    _check(lib().sw_profile_read(ms, launches, work))
+    return {CLASS_NAMES[i]: dict(ms=ms[i], launches=int(launches[i]), work=work[i]) for i in range(n)}
+
+
+# ---- convenience on top of the ABI (allocation of the workspace with torch; no arithmetic) ---------------------
+
+def matmul(A, B, levels, schedule=None, workspace=None):
+    """C = A @ B for square float64 CUDA tensors.  Allocates C and, if none is given, a workspace of exactly
+    sw_plan_memory bytes (schedule None -> the planner's choice for 80% of the free device memory)."""
+    import torch
+    _f64_cuda(A, "A")
+    _f64_cuda(B, "B")
+    n = A.shape[0]
+    A = A.contiguous()
+    B = B.contiguous()
+    C = torch.empty_like(A)
+    if workspace is None:
+        if schedule is None:
+            free, _ = torch.cuda.mem_get_info(A.device)
+            schedule = sw_plan_schedule(n, levels, int(free * 0.8))
+        need = sw_plan_memory(n, levels, schedule)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=A.device)
+    with torch.cuda.device(A.device):
+        sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, workspace)
+    return C

@@ -1,0 +1,334 @@
+// Streaming kernels of the Strassen-Winograd step: the pre-additions that form the T and S operands, the
+// post-additions that turn the seven products into the four quadrants of C (Appendix A), the element-wise
+// pieces of a DFS step, and the zero-padded copy.  All are HBM-bound: every kernel reads each input element
+// once and writes each output element once, with 16-byte accesses when alignment allows (8-byte otherwise).
+//
+// Thread layout, common to all kernels: threadIdx.x walks columns in units of VEC doubles, blockIdx.y walks
+// groups of ROWS rows, blockIdx.z is the matrix of the batch.  Adjacent lanes touch adjacent addresses, so a
+// wavefront reads and writes whole 512- or 1024-byte row segments.
+#include "sw_internal.h"
+
+namespace sw {
+namespace {
+
+constexpr int NT = 256;   // threads per block
+constexpr int ROWS = 4;   // rows per thread (independent loads in flight)
+
+template <int VEC> struct VecT;
+template <> struct VecT<1> { typedef double type; };
+template <> struct VecT<2> { typedef double __attribute__((ext_vector_type(2))) type; };
+
+template <int VEC>
+__device__ __forceinline__ typename VecT<VEC>::type ld(const double* p)
+{
+    return *reinterpret_cast<const typename VecT<VEC>::type*>(p);
+}
+template <int VEC>
+__device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
+{
+    *reinterpret_cast<typename VecT<VEC>::type*>(p) = v;
+}
+
+// ---- BFS pre-additions ------------------------------------------------------------------------------------
+// SIDE 0: T0 = A11, T1 = A12, T2 = A21 + A22, T3 = T2 - A11, T4 = A11 - A21, T5 = A12 - T3, T6 = A22
+// SIDE 1: S0 = B11, S1 = B21, S2 = B12 - B11, S3 = B22 - S2, S4 = B22 - B12, S5 = B22, S6 = S3 - B21
+template <int SIDE, int VEC>
+__global__ void __launch_bounds__(NT)
+pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int h,
+               double* __restrict__ child, int64_t cld, int64_t cstride)
+{
+    typedef typename VecT<VEC>::type V;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    if (cx >= h) return;
+    const int r0 = blockIdx.y * ROWS;
+    const double* P = parent + (int64_t)blockIdx.z * pstride;
+    double* O = child + (int64_t)blockIdx.z * 7 * cstride;
+
+    V q11[ROWS], q12[ROWS], q21[ROWS], q22[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            const double* top = P + (int64_t)row * pld + cx;
+            const double* bot = P + (int64_t)(row + h) * pld + cx;
+            q11[r] = ld<VEC>(top);
+            q12[r] = ld<VEC>(top + h);
+            q21[r] = ld<VEC>(bot);
+            q22[r] = ld<VEC>(bot + h);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            double* o = O + (int64_t)row * cld + cx;
+            if (SIDE == 0) {
+                const V t2 = q21[r] + q22[r];
+                const V t3 = t2 - q11[r];
+                const V t4 = q11[r] - q21[r];
+                const V t5 = q12[r] - t3;
+                st<VEC>(o, q11[r]);
+                st<VEC>(o + cstride, q12[r]);
+                st<VEC>(o + 2 * cstride, t2);
+                st<VEC>(o + 3 * cstride, t3);
+                st<VEC>(o + 4 * cstride, t4);
+                st<VEC>(o + 5 * cstride, t5);
+                st<VEC>(o + 6 * cstride, q22[r]);
+            } else {
+                const V s2 = q12[r] - q11[r];
+                const V s3 = q22[r] - s2;
+                const V s4 = q22[r] - q12[r];
+                const V s6 = s3 - q21[r];
+                st<VEC>(o, q11[r]);
+                st<VEC>(o + cstride, q21[r]);
+                st<VEC>(o + 2 * cstride, s2);
+                st<VEC>(o + 3 * cstride, s3);
+                st<VEC>(o + 4 * cstride, s4);
+                st<VEC>(o + 5 * cstride, q22[r]);
+                st<VEC>(o + 6 * cstride, s6);
+            }
+        }
+    }
+}
+
+// ---- BFS post-additions -----------------------------------------------------------------------------------
+// U1 = Q0 + Q3, U2 = U1 + Q4, U3 = U1 + Q2, C11 = Q0 + Q1, C12 = U3 + Q5, C21 = U2 - Q6, C22 = U2 + Q2
+template <int VEC>
+__global__ void __launch_bounds__(NT)
+post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int h,
+                double* __restrict__ parent, int64_t pld, int64_t pstride)
+{
+    typedef typename VecT<VEC>::type V;
+    constexpr int R = 2;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    if (cx >= h) return;
+    const int r0 = blockIdx.y * R;
+    const double* q = Q + (int64_t)blockIdx.z * 7 * qstride;
+    double* P = parent + (int64_t)blockIdx.z * pstride;
+
+    V v[R][7];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+#pragma unroll
+            for (int j = 0; j < 7; ++j) v[r][j] = ld<VEC>(q + j * qstride + (int64_t)row * qld + cx);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            const V u1 = v[r][0] + v[r][3];
+            const V u2 = u1 + v[r][4];
+            const V u3 = u1 + v[r][2];
+            double* top = P + (int64_t)row * pld + cx;
+            double* bot = P + (int64_t)(row + h) * pld + cx;
+            st<VEC>(top, v[r][0] + v[r][1]);
+            st<VEC>(top + h, u3 + v[r][5]);
+            st<VEC>(bot, u2 - v[r][6]);
+            st<VEC>(bot + h, u2 + v[r][2]);
+        }
+    }
+}
+
+// ---- element-wise pieces of a DFS step ------------------------------------------------------------------------
+
+struct EwOp {
+    double* z;
+    const double* x;
+    const double* y;
+    int64_t zld, xld, yld;
+    int64_t zstride, xstride, ystride;
+    int sign;
+};
+
+// NOPS independent operations Z = X + sign * Y; blockIdx.z = op * live + matrix.  Z may alias X or Y
+// exactly (same element, same thread), so no __restrict__ here.
+template <int VEC, int NOPS>
+__global__ void __launch_bounds__(NT)
+ew_kernel(EwOp op0, EwOp op1, int live, int h)
+{
+    typedef typename VecT<VEC>::type V;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    if (cx >= h) return;
+    const int r0 = blockIdx.y * ROWS;
+    int b = blockIdx.z;
+    const bool second = NOPS == 2 && b >= live;
+    if (second) b -= live;
+    const EwOp& op = second ? op1 : op0;
+    double* z = op.z + (int64_t)b * op.zstride;
+    const double* x = op.x + (int64_t)b * op.xstride;
+    const double* y = op.y + (int64_t)b * op.ystride;
+    V xv[ROWS], yv[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            xv[r] = ld<VEC>(x + (int64_t)row * op.xld + cx);
+            yv[r] = ld<VEC>(y + (int64_t)row * op.yld + cx);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = r0 + r;
+        if (row < h) st<VEC>(z + (int64_t)row * op.zld + cx, op.sign > 0 ? xv[r] + yv[r] : xv[r] - yv[r]);
+    }
+}
+
+// With X = Q0, C12 = Q3, C21 = Q4, C22 = Q2, C11 = Q5:
+//   U1 = X + C12, U2 = U1 + C21, U3 = U1 + C22, C22 <- U2 + C22, C12 <- U3 + C11, C21 <- U2
+// (Appendix A column 4 in its printed association; C21 still lacks - Q6 and C11 is rewritten later).
+template <int VEC>
+__global__ void __launch_bounds__(NT)
+dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11, double* c12, double* c21,
+                double* c22, int64_t cld, int64_t cstride, int h)
+{
+    typedef typename VecT<VEC>::type V;
+    constexpr int R = 2;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    if (cx >= h) return;
+    const int r0 = blockIdx.y * R;
+    const int64_t boff = (int64_t)blockIdx.z * cstride;
+    x += (int64_t)blockIdx.z * xstride;
+    V q0[R], q5[R], q3[R], q4[R], q2[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            const int64_t o = boff + (int64_t)row * cld + cx;
+            q0[r] = ld<VEC>(x + (int64_t)row * xld + cx);
+            q5[r] = ld<VEC>(c11 + o);
+            q3[r] = ld<VEC>(c12 + o);
+            q4[r] = ld<VEC>(c21 + o);
+            q2[r] = ld<VEC>(c22 + o);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = r0 + r;
+        if (row < h) {
+            const int64_t o = boff + (int64_t)row * cld + cx;
+            const V u1 = q0[r] + q3[r];
+            const V u2 = u1 + q4[r];
+            const V u3 = u1 + q2[r];
+            st<VEC>(c22 + o, u2 + q2[r]);
+            st<VEC>(c12 + o, u3 + q5[r]);
+            st<VEC>(c21 + o, u2);
+        }
+    }
+}
+
+// ---- zero-padded copy ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT)
+pad_copy_kernel(const double* __restrict__ src, int64_t sld, int rows, int cols, double* __restrict__ dst,
+                int64_t dld, int prows, int pcols)
+{
+    const int c = blockIdx.x * NT + threadIdx.x;
+    if (c >= pcols) return;
+    const int r0 = blockIdx.y * ROWS;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = r0 + r;
+        if (row < prows) {
+            const double v = (row < rows && c < cols) ? src[(int64_t)row * sld + c] : 0.0;
+            dst[(int64_t)row * dld + c] = v;
+        }
+    }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool even(int64_t v) { return (v & 1) == 0; }
+inline bool mat_vec2(const Mat& m) { return aligned16(m.p) && even(m.ld) && even(m.stride); }
+
+inline dim3 grid_for(int64_t h, int vec, int rows, int64_t batch)
+{
+    const int64_t chunks = (h + vec - 1) / vec;
+    return dim3((unsigned)((chunks + NT - 1) / NT), (unsigned)((h + rows - 1) / rows), (unsigned)batch);
+}
+
+}  // namespace
+
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, hipStream_t s)
+{
+    if (live == 0 || h == 0) return hipSuccess;
+    const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(child);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, live);
+#define SW_LAUNCH(SIDE, VEC)                                                                              \
+    hipLaunchKernelGGL((pre_add_kernel<SIDE, VEC>), g, dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
+                       (int)h, child.p, child.ld, child.stride)
+    if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
+    else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
+#undef SW_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s)
+{
+    if (live == 0 || h == 0) return hipSuccess;
+    const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(q);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, 2, live);
+    if (v2)
+        hipLaunchKernelGGL((post_add_kernel<2>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+                           parent.ld, parent.stride);
+    else
+        hipLaunchKernelGGL((post_add_kernel<1>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+                           parent.ld, parent.stride);
+    return hipGetLastError();
+}
+
+static EwOp make_op(Mat z, Mat x, Mat y, int sign)
+{
+    return EwOp{z.p, x.p, y.p, z.ld, x.ld, y.ld, z.stride, x.stride, y.stride, sign};
+}
+
+hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s)
+{
+    if (live == 0 || h == 0) return hipSuccess;
+    const bool v2 = even(h) && mat_vec2(z) && mat_vec2(x) && mat_vec2(y);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, live);
+    const EwOp op = make_op(z, x, y, sign);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 1>), g, dim3(NT), 0, s, op, op, (int)live, (int)h);
+    else    hipLaunchKernelGGL((ew_kernel<1, 1>), g, dim3(NT), 0, s, op, op, (int)live, (int)h);
+    return hipGetLastError();
+}
+
+hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1, int sign1, int64_t live,
+                      int64_t h, hipStream_t s)
+{
+    if (live == 0 || h == 0) return hipSuccess;
+    const bool v2 = even(h) && mat_vec2(z0) && mat_vec2(x0) && mat_vec2(y0) && mat_vec2(z1) && mat_vec2(x1) &&
+                    mat_vec2(y1);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, 2 * live);
+    const EwOp a = make_op(z0, x0, y0, sign0), b = make_op(z1, x1, y1, sign1);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 2>), g, dim3(NT), 0, s, a, b, (int)live, (int)h);
+    else    hipLaunchKernelGGL((ew_kernel<1, 2>), g, dim3(NT), 0, s, a, b, (int)live, (int)h);
+    return hipGetLastError();
+}
+
+hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t h, hipStream_t s)
+{
+    if (live == 0 || h == 0) return hipSuccess;
+    // the four quadrants share ld and stride by construction
+    const bool v2 = even(h) && mat_vec2(x) && mat_vec2(c11) && mat_vec2(c12) && mat_vec2(c21) && mat_vec2(c22);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, 2, live);
+    if (v2)
+        hipLaunchKernelGGL((dfs_post_kernel<2>), g, dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
+                           c22.p, c11.ld, c11.stride, (int)h);
+    else
+        hipLaunchKernelGGL((dfs_post_kernel<1>), g, dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
+                           c22.p, c11.ld, c11.stride, (int)h);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst,
+                           int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s)
+{
+    if (prows == 0 || pcols == 0) return hipSuccess;
+    const dim3 g((unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + ROWS - 1) / ROWS), 1);
+    hipLaunchKernelGGL(pad_copy_kernel, g, dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
+                       (int)prows, (int)pcols);
+    return hipGetLastError();
+}
+
+}  // namespace sw

@@ -1,0 +1,491 @@
+// Host side of the library: the C ABI of include/sw_gemm.h, the BFS/DFS schedule planner and the executor
+// that walks the recursion tree and enqueues kernels on one HIP stream.  No device memory is allocated here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "sw_internal.h"
+
+namespace sw {
+
+// ---- error text ---------------------------------------------------------------------------------------------
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char* what)
+{
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return SW_EHIP;
+}
+
+// ---- library state --------------------------------------------------------------------------------------------
+
+static void* g_ws = nullptr;
+static int64_t g_ws_bytes = 0;
+static hipStream_t g_stream = nullptr;
+
+// ---- profiling ------------------------------------------------------------------------------------------------
+
+struct Profiler {
+    struct Rec { hipEvent_t e0, e1; int cls; double work; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t take()
+    {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+
+static Profiler g_prof;
+static bool g_prof_on = false;
+
+Profiler* profiler() { return g_prof_on ? &g_prof : nullptr; }
+
+void prof_begin(Profiler* p, hipStream_t s, int cls, double work)
+{
+    if (!p) return;
+    Profiler::Rec r{p->take(), p->take(), cls, work};
+    if (r.e0) (void)hipEventRecord(r.e0, s);
+    p->recs.push_back(r);
+}
+
+void prof_end(Profiler* p, hipStream_t s)
+{
+    if (!p || p->recs.empty()) return;
+    if (p->recs.back().e1) (void)hipEventRecord(p->recs.back().e1, s);
+}
+
+// ---- schedule checks and the planner ------------------------------------------------------------------------------
+
+static bool schedule_ok(const char* s, int levels)
+{
+    if ((int)strlen(s) != levels) return false;
+    for (int i = 0; i < levels; ++i)
+        if (s[i] != 'B' && s[i] != 'D') return false;
+    return true;
+}
+
+static int check_shape(int64_t n, int levels)
+{
+    if (n < 0 || levels < 0 || levels > SW_MAX_LEVELS) {
+        set_error("bad shape: n = %lld, levels = %d (0 <= levels <= %d)", (long long)n, levels, SW_MAX_LEVELS);
+        return SW_EINVAL;
+    }
+    if (n > 0 && ((int64_t)1 << levels) > n) {
+        set_error("2^levels = %lld exceeds n = %lld", (long long)((int64_t)1 << levels), (long long)n);
+        return SW_EINVAL;
+    }
+    if (n > 200000) {
+        set_error("n = %lld is above the supported maximum of 200000", (long long)n);
+        return SW_EINVAL;
+    }
+    return SW_OK;
+}
+
+// Total workspace bytes for (n, schedule), including padded copies of A, B, C when needed.
+static int64_t total_need(int64_t n, int levels, const char* sched)
+{
+    if (n == 0) return 0;
+    const int64_t np = padded_n(n, levels);
+    int64_t bytes = ws_need_bytes(np, sched, 1);
+    if (np != n) bytes += 3 * ws_mat_elems(np) * (int64_t)sizeof(double);
+    return bytes;
+}
+
+static int plan(int64_t n, int levels, int64_t budget, char* out)
+{
+    // Enumerate all step orders.  Preference: most BFS steps (largest leaf batch per launch, fewest
+    // launches), then least memory, which puts the DFS steps first (the Limited-Memory shape of Section 3.4).
+    char cand[SW_MAX_LEVELS + 1];
+    int best_b = -1;
+    int64_t best_need = 0;
+    for (uint32_t mask = 0; mask < (1u << levels); ++mask) {
+        int nb = 0;
+        for (int i = 0; i < levels; ++i) {
+            const bool b = (mask >> i) & 1u;
+            cand[i] = b ? 'B' : 'D';
+            nb += b;
+        }
+        cand[levels] = '\0';
+        const int64_t need = total_need(n, levels, cand);
+        if (need > budget) continue;
+        if (nb > best_b || (nb == best_b && need < best_need)) {
+            best_b = nb;
+            best_need = need;
+            memcpy(out, cand, (size_t)levels + 1);
+        }
+    }
+    if (best_b < 0) {
+        set_error("no step order for n = %lld, levels = %d fits a workspace of %lld bytes (all-DFS needs %lld)",
+                  (long long)n, levels, (long long)budget,
+                  (long long)total_need(n, levels, std::string((size_t)levels, 'D').c_str()));
+        return SW_ENOMEM;
+    }
+    return SW_OK;
+}
+
+// ---- the executor ----------------------------------------------------------------------------------------------
+
+struct Exec {
+    hipStream_t stream;
+    char* ws;
+    int64_t ws_bytes;
+    int64_t used = 0;
+    const char* sched;
+    int levels;
+    Profiler* prof;
+    hipError_t err = hipSuccess;
+
+    double* take(int64_t elems)
+    {
+        double* p = reinterpret_cast<double*>(ws + used);
+        used += elems * (int64_t)sizeof(double);
+        return p;
+    }
+
+    void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+
+    // bytes moved by an element-wise kernel with `nin` input and `nout` output matrices of h x h
+    static double bytes(int64_t live, int64_t h, int nin, int nout) { return 8.0 * live * h * h * (nin + nout); }
+
+    void ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h)
+    {
+        prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 2, 1));
+        note(launch_ew(z, x, y, sign, live, h, stream));
+        prof_end(prof, stream);
+    }
+
+    void ew2(Mat z0, Mat x0, Mat y0, int s0, Mat z1, Mat x1, Mat y1, int s1, int64_t live, int64_t h)
+    {
+        prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 4, 2));
+        note(launch_ew2(z0, x0, y0, s0, z1, x1, y1, s1, live, h, stream));
+        prof_end(prof, stream);
+    }
+
+    // C = A * B for `live` independent n x n problems, steps sched[level..] (Algorithm 2: procedures DFS and BFS).
+    void mul(Mat A, Mat B, Mat C, int64_t n, int level, int64_t live)
+    {
+        if (err != hipSuccess) return;
+        if (level == levels) {
+            prof_begin(prof, stream, SW_CLASS_LEAF, 2.0 * live * (double)n * (double)n * (double)n);
+            note(launch_leaf_gemm(n, live, A, B, C, stream));
+            prof_end(prof, stream);
+            return;
+        }
+        const int64_t h = n / 2;
+        const int64_t ld = ws_ld(h), e = ws_mat_elems(h);
+        const int64_t mark = used;
+        if (sched[level] == 'B') {
+            // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
+            Mat T{take(7 * live * e), ld, e}, S{take(7 * live * e), ld, e}, Q{take(7 * live * e), ld, e};
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
+            note(launch_pre_add(0, A, live, h, T, stream));
+            prof_end(prof, stream);
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
+            note(launch_pre_add(1, B, live, h, S, stream));
+            prof_end(prof, stream);
+            mul(T, S, Q, h, level + 1, 7 * live);
+            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, h, 7, 4));
+            note(launch_post_add(Q, live, h, C, stream));
+            prof_end(prof, stream);
+        } else {
+            // DFS step: the seven products one after the other (Section 3.4), written straight into the
+            // quadrants of C, with two temporaries X, Y per parent.  The additions are those of Appendix A
+            // in the printed association, so the result is bit-identical to the BFS form.
+            Mat X{take(live * e), ld, e}, Y{take(live * e), ld, e};
+            const Mat A11 = quad(A, h, 0, 0), A12 = quad(A, h, 0, 1), A21 = quad(A, h, 1, 0), A22 = quad(A, h, 1, 1);
+            const Mat B11 = quad(B, h, 0, 0), B12 = quad(B, h, 0, 1), B21 = quad(B, h, 1, 0), B22 = quad(B, h, 1, 1);
+            const Mat C11 = quad(C, h, 0, 0), C12 = quad(C, h, 0, 1), C21 = quad(C, h, 1, 0), C22 = quad(C, h, 1, 1);
+            ew2(X, A11, A21, -1, Y, B22, B12, -1, live, h);     // T4 = A11 - A21, S4 = B22 - B12
+            mul(X, Y, C21, h, level + 1, live);                 // C21 <- Q4
+            ew2(X, A21, A22, +1, Y, B12, B11, -1, live, h);     // T2 = A21 + A22, S2 = B12 - B11
+            mul(X, Y, C22, h, level + 1, live);                 // C22 <- Q2
+            ew2(X, X, A11, -1, Y, B22, Y, -1, live, h);         // T3 = T2 - A11,  S3 = B22 - S2
+            mul(X, Y, C12, h, level + 1, live);                 // C12 <- Q3
+            ew(X, A12, X, -1, live, h);                         // T5 = A12 - T3
+            mul(X, B22, C11, h, level + 1, live);               // C11 <- Q5 = T5 * B22
+            mul(A11, B11, X, h, level + 1, live);               // X   <- Q0 = A11 * B11
+            prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 5, 3));
+            note(launch_dfs_post(X, C11, C12, C21, C22, live, h, stream));  // C12, C22 final; C21 = U2
+            prof_end(prof, stream);
+            ew(Y, Y, B21, -1, live, h);                         // S6 = S3 - B21
+            mul(A22, Y, C11, h, level + 1, live);               // C11 <- Q6 = A22 * S6
+            ew(C21, C21, C11, -1, live, h);                     // C21 = U2 - Q6
+            mul(A12, B21, C11, h, level + 1, live);             // C11 <- Q1 = A12 * B21
+            ew(C11, X, C11, +1, live, h);                       // C11 = Q0 + Q1
+        }
+        used = mark;
+    }
+};
+
+static bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
+{
+    const uintptr_t a0 = (uintptr_t)p, a1 = a0 + (uintptr_t)pn * sizeof(double);
+    const uintptr_t b0 = (uintptr_t)q, b1 = b0 + (uintptr_t)qn * sizeof(double);
+    return a0 < b1 && b0 < a1;
+}
+
+static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                     int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
+{
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    if (n == 0) return SW_OK;
+    if (!A || !B || !C) { set_error("NULL matrix pointer"); return SW_EINVAL; }
+    if (lda < n || ldb < n || ldc < n) { set_error("leading dimension smaller than n"); return SW_EINVAL; }
+    const int64_t spanA = (n - 1) * lda + n, spanB = (n - 1) * ldb + n, spanC = (n - 1) * ldc + n;
+    if (overlaps(C, spanC, A, spanA) || overlaps(C, spanC, B, spanB)) {
+        set_error("C overlaps A or B");
+        return SW_EINVAL;
+    }
+    char chosen[SW_MAX_LEVELS + 1];
+    if (!schedule || !*schedule) {
+        rc = plan(n, levels, ws ? ws_bytes : 0, chosen);
+        if (rc != SW_OK) return rc;
+        schedule = chosen;
+    } else if (!schedule_ok(schedule, levels)) {
+        set_error("schedule \"%s\" must be %d characters of B or D", schedule, levels);
+        return SW_EINVAL;
+    }
+    const int64_t need = total_need(n, levels, schedule);
+    if (need > 0) {
+        if (!ws || ws_bytes < need) {
+            set_error("workspace of %lld bytes is too small: n = %lld, schedule %s needs %lld", (long long)(ws ? ws_bytes : 0),
+                      (long long)n, schedule, (long long)need);
+            return SW_ENOMEM;
+        }
+        if ((uintptr_t)ws & 255u) { set_error("workspace must be 256-byte aligned"); return SW_EINVAL; }
+        if (overlaps((const double*)ws, need / 8, A, spanA) || overlaps((const double*)ws, need / 8, B, spanB) ||
+            overlaps((const double*)ws, need / 8, C, spanC)) {
+            set_error("workspace overlaps A, B or C");
+            return SW_EINVAL;
+        }
+    }
+
+    Exec ex;
+    ex.stream = stream;
+    ex.ws = (char*)ws;
+    ex.ws_bytes = ws_bytes;
+    ex.sched = schedule;
+    ex.levels = levels;
+    ex.prof = profiler();
+
+    const int64_t np = padded_n(n, levels);
+    Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
+    if (np != n) {
+        // zero-pad into workspace copies of the next multiple of 2^levels (Section 3.1)
+        const int64_t ld = ws_ld(np), e = ws_mat_elems(np);
+        a = Mat{ex.take(e), ld, 0};
+        b = Mat{ex.take(e), ld, 0};
+        c = Mat{ex.take(e), ld, 0};
+        prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np));
+        ex.note(launch_pad_copy(A, lda, n, n, a.p, ld, np, np, stream));
+        ex.note(launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, stream));
+        prof_end(ex.prof, stream);
+    }
+    ex.mul(a, b, c, np, 0, 1);
+    if (np != n) {
+        prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * 2.0 * n * n);
+        ex.note(launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, stream));
+        prof_end(ex.prof, stream);
+    }
+    if (ex.err != hipSuccess) return hip_fail(ex.err, "kernel launch");
+    return SW_OK;
+}
+
+}  // namespace sw
+
+using namespace sw;
+
+// ================================================ C ABI ==========================================================
+
+extern "C" {
+
+int sw_gemm(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule)
+{
+    return gemm_impl(n, A, n, B, n, C, n, levels, schedule, g_ws, g_ws_bytes, g_stream);
+}
+
+int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+               int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream)
+{
+    if (workspace_bytes < 0) { set_error("negative workspace size"); return SW_EINVAL; }
+    return gemm_impl(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int64_t sw_plan_memory(int64_t n, int levels, const char* schedule)
+{
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    std::string s = (schedule && *schedule) ? std::string(schedule) : std::string((size_t)levels, 'D');
+    if (!schedule_ok(s.c_str(), levels)) {
+        set_error("schedule \"%s\" must be %d characters of B or D", s.c_str(), levels);
+        return SW_EINVAL;
+    }
+    return total_need(n, levels, s.c_str());
+}
+
+int sw_plan_schedule(int64_t n, int levels, int64_t budget_bytes, char* out)
+{
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    if (!out) { set_error("NULL output buffer"); return SW_EINVAL; }
+    if (budget_bytes < 0) { set_error("negative budget"); return SW_EINVAL; }
+    return plan(n, levels, budget_bytes, out);
+}
+
+int64_t sw_model_words(int64_t n, int levels, const char* schedule)
+{
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    if (!schedule || !schedule_ok(schedule, levels)) { set_error("bad schedule"); return SW_EINVAL; }
+    if (n % ((int64_t)1 << levels)) { set_error("n is not a multiple of 2^levels"); return SW_EINVAL; }
+    int64_t words = 3 * n * n, live = 1, size = n;
+    for (int i = 0; i < levels; ++i) {
+        if (schedule[i] == 'B') live *= 7;
+        size /= 2;
+        words += 3 * live * size * size;
+    }
+    return words;
+}
+
+int sw_lm_dfs_steps(double n, double P, double M_words)
+{
+    if (!(n > 0) || !(P >= 1) || !(M_words > 0)) { set_error("bad argument"); return SW_EINVAL; }
+    const double w0 = log2(7.0);
+    const double l = ceil(log2(4.0 * n / (pow(P, 1.0 / w0) * sqrt(M_words))));
+    return l > 0 ? (int)l : 0;
+}
+
+double sw_flop_count(int64_t n, int levels)
+{
+    if (check_shape(n, levels) != SW_OK || n % ((int64_t)1 << levels)) return -1.0;
+    const double m = (double)(n >> levels);
+    double leaves = 1.0, adds = 0.0, size = (double)n;
+    for (int i = 0; i < levels; ++i) {
+        adds += 15.0 * leaves * (size / 2) * (size / 2);
+        leaves *= 7.0;
+        size /= 2;
+    }
+    return leaves * (2.0 * m * m * m - m * m) + adds;
+}
+
+int sw_set_workspace(void* dev_ptr, int64_t bytes)
+{
+    if (bytes < 0 || (!dev_ptr && bytes != 0)) { set_error("bad workspace"); return SW_EINVAL; }
+    if ((uintptr_t)dev_ptr & 255u) { set_error("workspace must be 256-byte aligned"); return SW_EINVAL; }
+    g_ws = dev_ptr;
+    g_ws_bytes = bytes;
+    return SW_OK;
+}
+
+int sw_set_stream(void* hip_stream)
+{
+    g_stream = (hipStream_t)hip_stream;
+    return SW_OK;
+}
+
+const char* sw_last_error(void) { return g_err; }
+
+// ---- single steps -------------------------------------------------------------------------------------------------
+
+static bool bad_dims(int64_t live, int64_t h) { return live < 0 || h < 0 || h > 131070 || live > 65535; }
+
+int sw_pre_add(int side, const double* parent, int64_t parent_ld, int64_t parent_stride, int64_t live,
+               int64_t h, double* child, int64_t child_ld, int64_t child_stride, void* hip_stream)
+{
+    if ((side != 0 && side != 1) || bad_dims(live, h) || !parent || !child || parent_ld < 2 * h || child_ld < h) {
+        set_error("sw_pre_add: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_pre_add(side, Mat{const_cast<double*>(parent), parent_ld, parent_stride}, live, h,
+                                  Mat{child, child_ld, child_stride}, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_pre_add");
+}
+
+int sw_post_add(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, int64_t h, double* parent,
+                int64_t parent_ld, int64_t parent_stride, void* hip_stream)
+{
+    if (bad_dims(live, h) || !Q || !parent || parent_ld < 2 * h || q_ld < h) {
+        set_error("sw_post_add: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_post_add(Mat{const_cast<double*>(Q), q_ld, q_stride}, live, h,
+                                   Mat{parent, parent_ld, parent_stride}, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_post_add");
+}
+
+int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t stride_a, const double* B,
+                 int64_t ldb, int64_t stride_b, double* C, int64_t ldc, int64_t stride_c, void* hip_stream)
+{
+    if (m < 0 || batch < 0 || m > 200000 || !A || !B || !C || lda < m || ldb < m || ldc < m) {
+        set_error("sw_leaf_gemm: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_leaf_gemm(m, batch, Mat{const_cast<double*>(A), lda, stride_a},
+                                    Mat{const_cast<double*>(B), ldb, stride_b}, Mat{C, ldc, stride_c},
+                                    (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_leaf_gemm");
+}
+
+int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst, int64_t dst_ld,
+                int64_t prows, int64_t pcols, void* hip_stream)
+{
+    if (!src || !dst || rows < 0 || cols < 0 || prows < 0 || pcols < 0 || src_ld < cols || dst_ld < pcols ||
+        prows > 262140 || pcols > 0x7fffffff) {
+        set_error("sw_pad_copy: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_pad_copy(src, src_ld, rows, cols, dst, dst_ld, prows, pcols, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_pad_copy");
+}
+
+// ---- measurement ----------------------------------------------------------------------------------------------------
+
+int sw_profile_enable(int on)
+{
+    g_prof_on = on != 0;
+    return SW_OK;
+}
+
+int sw_profile_read(double* ms, int64_t* launches, double* work)
+{
+    if (!ms || !launches || !work) { set_error("NULL output"); return SW_EINVAL; }
+    for (int i = 0; i < SW_NUM_CLASSES; ++i) { ms[i] = 0.0; launches[i] = 0; work[i] = 0.0; }
+    hipError_t bad = hipSuccess;
+    for (auto& r : g_prof.recs) {
+        if (r.e0 && r.e1) {
+            float t = 0.f;
+            hipError_t e = hipEventSynchronize(r.e1);
+            if (e == hipSuccess) e = hipEventElapsedTime(&t, r.e0, r.e1);
+            if (e == hipSuccess) {
+                ms[r.cls] += (double)t;
+                launches[r.cls] += 1;
+                work[r.cls] += r.work;
+            } else if (bad == hipSuccess) {
+                bad = e;
+            }
+        }
+        if (r.e0) g_prof.pool.push_back(r.e0);
+        if (r.e1) g_prof.pool.push_back(r.e1);
+    }
+    g_prof.recs.clear();
+    return bad == hipSuccess ? SW_OK : hip_fail(bad, "sw_profile_read");
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the host planner, the executor and the kernel launchers.
+// Nothing here is visible through the C ABI (include/sw_gemm.h).
+#pragma once
+
+#include <stdint.h>
+
+#include <hip/hip_runtime.h>
+
+#include "sw_gemm.h"
+
+namespace sw {
+
+// ---- workspace layout rules (used by BOTH the planner and the executor, so they cannot disagree) ---------
+
+// Leading dimension of an h-column matrix the library places in its workspace: a multiple of 16 doubles
+// (every row starts on a 128-byte line), and never a multiple of 256 doubles (rows of a power-of-two pitch
+// would all fall on the same HBM channels).
+inline int64_t ws_ld(int64_t h)
+{
+    int64_t ld = (h + 15) / 16 * 16;
+    if (ld >= 256 && ld % 256 == 0) ld += 16;
+    return ld;
+}
+
+// Elements reserved for one h x h workspace matrix (a multiple of 32 doubles = 256 bytes).
+inline int64_t ws_mat_elems(int64_t h) { return (ws_ld(h) * h + 31) / 32 * 32; }
+
+// Bytes of workspace the executor takes for an np x np problem (np a multiple of 2^levels) whose remaining
+// step order is `sched`, entered with `live` parents.  BFS step: T, S, Q for all seven children of every
+// parent (Section 3.3.1); DFS step: two temporaries per parent, because products are written straight into
+// the parent's C quadrants (the footnote of Section 3.3.1 allows a few temporaries).
+inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live)
+{
+    if (*sched == '\0') return 0;
+    const int64_t h = n / 2;
+    const int64_t e = ws_mat_elems(h) * (int64_t)sizeof(double);
+    if (*sched == 'B') return 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live);
+    return 2 * live * e + ws_need_bytes(h, sched + 1, live);
+}
+
+inline int64_t padded_n(int64_t n, int levels)
+{
+    const int64_t q = (int64_t)1 << levels;
+    return (n + q - 1) / q * q;
+}
+
+// ---- error text ---------------------------------------------------------------------------------------------
+
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+// ---- profiling record (sw_profile_enable / sw_profile_read) ---------------------------------------------------
+
+struct Profiler;
+Profiler* profiler();                                  // nullptr when profiling is off
+void prof_begin(Profiler*, hipStream_t, int cls, double work);
+void prof_end(Profiler*, hipStream_t);
+
+// ---- a batch of equally shaped matrices: matrix b starts at p + b * stride, rows ld apart ----------------------
+
+struct Mat {
+    double* p;
+    int64_t ld;
+    int64_t stride;
+};
+
+inline Mat quad(const Mat& m, int64_t h, int i, int j) { return Mat{m.p + i * h * m.ld + j * h, m.ld, m.stride}; }
+
+// ---- kernel launchers (each validates nothing: callers pass consistent shapes) --------------------------------
+
+// BFS pre-additions, Appendix A columns 1 (side 0, T from A) and 2 (side 1, S from B).
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, hipStream_t s);
+// BFS post-additions, Appendix A column 4.
+hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s);
+// Z = X + sign * Y on h x h matrices, `live` of them; Z may be X or Y itself.
+hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s);
+// Two independent such operations in one launch (the A-side and B-side pre-addition of a DFS step).
+hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1, int sign1, int64_t live,
+                      int64_t h, hipStream_t s);
+// DFS post-addition block: with X = Q0, C12 = Q3, C21 = Q4, C22 = Q2, C11 = Q5 on entry,
+// U1 = X + C12, U2 = U1 + C21, U3 = U1 + C22, then C22 = U2 + C22, C12 = U3 + C11, C21 = U2.
+hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t h, hipStream_t s);
+// Zero-padded copy / crop.
+hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst,
+                           int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s);
+// Batched classical product on the fp64 matrix cores.
+hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s);
+
+}  // namespace sw

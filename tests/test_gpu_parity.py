@@ -1,0 +1,253 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on seeded inputs.
+
+Bar: fp64 results within max|C - C_ref| <= 1e-10 * n * max|A| * max|B| (the build's stated tolerance, whose
+form is the norm-wise bound of Section 6.1); integer-valued inputs, for which every intermediate of the
+recursion is an exactly representable integer, must agree BIT FOR BIT with the oracle and with the exact
+product; results must not depend on the BFS/DFS order at all.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_1202_3173_amd import binding as sw
+from paper_1202_3173_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def tol(n, A, B):
+    return 1e-10 * n * float(np.max(np.abs(A))) * float(np.max(np.abs(B)))
+
+
+def run(A, B, levels, schedule):
+    n = A.shape[0]
+    dA = torch.from_numpy(A).to(DEV)
+    dB = torch.from_numpy(B).to(DEV)
+    C = sw.matmul(dA, dB, levels, schedule)
+    torch.cuda.synchronize()
+    assert torch.equal(dA.cpu(), torch.from_numpy(A)) and torch.equal(dB.cpu(), torch.from_numpy(B)), "inputs changed"
+    return C.cpu().numpy()
+
+
+# ---- the generator is the same on host and device --------------------------------------------------------------
+
+@pytest.mark.parametrize("dist", ["uniform", "rowscaled", "integer"])
+def test_device_generator_matches_host(dist):
+    n = 333
+    for which in (0, 1):
+        t = torch.empty((n, n), dtype=torch.float64, device=DEV)
+        inputs.fill_device(t, n, 42, which, dist)
+        torch.cuda.synchronize()
+        assert np.array_equal(t.cpu().numpy(), inputs.matrix(n, 42, which, dist))
+
+
+# ---- leaf products ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("m,batch,ldpad", [(1, 1, 0), (16, 3, 0), (100, 2, 0), (128, 1, 0), (129, 2, 1),
+                                           (255, 1, 1), (256, 2, 0), (300, 3, 4), (735, 2, 1), (514, 1, 2)])
+def test_leaf_gemm_against_classical_oracle(oracle, m, batch, ldpad):
+    ld = m + ldpad
+    stride = ld * m + 7 * (ldpad % 2)      # odd strides force the 8-byte load path
+    hA = [inputs.matrix(m, 3 + b, 0, "uniform") for b in range(batch)]
+    hB = [inputs.matrix(m, 3 + b, 1, "uniform") for b in range(batch)]
+    A = torch.zeros(batch * stride, dtype=torch.float64, device=DEV)
+    B = torch.zeros(batch * stride, dtype=torch.float64, device=DEV)
+    C = torch.full((batch * stride,), float("nan"), dtype=torch.float64, device=DEV)
+    for b in range(batch):
+        A[b * stride: b * stride + ld * m].view(m, ld)[:, :m] = torch.from_numpy(hA[b]).to(DEV)
+        B[b * stride: b * stride + ld * m].view(m, ld)[:, :m] = torch.from_numpy(hB[b]).to(DEV)
+    sw.sw_leaf_gemm(m, batch, A, ld, stride, B, ld, stride, C, ld, stride)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        got = C[b * stride: b * stride + ld * m].view(m, ld)[:, :m].cpu().numpy()
+        ref = oracle.naive(hA[b], hB[b])
+        assert np.max(np.abs(got - ref)) <= tol(m, hA[b], hB[b])
+        assert np.max(np.abs(got - ref)) <= 4 * m * np.finfo(float).eps   # classical: a few ulps per term
+        pad = C[b * stride: b * stride + ld * m].view(m, ld)[:, m:]
+        assert torch.isnan(pad).all(), "wrote outside the m x m result"
+
+
+def test_leaf_gemm_integer_exact(oracle):
+    for m in (64, 200, 735):
+        hA = inputs.matrix(m, 1, 0, "integer")
+        hB = inputs.matrix(m, 1, 1, "integer")
+        A, B = torch.from_numpy(hA).to(DEV), torch.from_numpy(hB).to(DEV)
+        C = torch.empty_like(A)
+        sw.sw_leaf_gemm(m, 1, A, m, 0, B, m, 0, C, m, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), oracle.naive(hA, hB))
+        assert np.array_equal(C.cpu().numpy(), (hA.astype(np.int64) @ hB.astype(np.int64)).astype(np.float64))
+
+
+# ---- one BFS step's additions, bit for bit (additions are exactly rounded, association as in Appendix A) -----------
+
+@pytest.mark.parametrize("h,live", [(8, 1), (97, 3), (128, 7), (735, 2), (300, 1)])
+def test_pre_and_post_add_bitwise(h, live):
+    n = 2 * h
+    ld = (h + 15) // 16 * 16
+    cs = ld * h + 32
+    P = torch.from_numpy(np.stack([inputs.matrix(n, 50 + p, 0, "uniform") for p in range(live)])).to(DEV)
+    hP = P.cpu().numpy()
+    q = lambda M, i, j: M[:, i * h:(i + 1) * h, j * h:(j + 1) * h]
+    a11, a12, a21, a22 = q(hP, 0, 0), q(hP, 0, 1), q(hP, 1, 0), q(hP, 1, 1)
+    for side in (0, 1):
+        out = torch.full((live * 7 * cs,), float("nan"), dtype=torch.float64, device=DEV)
+        sw.sw_pre_add(side, P, n, n * n, live, h, out, ld, cs)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().reshape(live, 7, cs)[:, :, :ld * h].reshape(live, 7, h, ld)
+        assert np.isnan(got[..., h:]).all()
+        got = got[..., :h]
+        if side == 0:
+            t2 = a21 + a22; t3 = t2 - a11; t4 = a11 - a21; t5 = a12 - t3
+            want = [a11, a12, t2, t3, t4, t5, a22]
+        else:
+            s2 = a12 - a11; s3 = a22 - s2; s4 = a22 - a12; s6 = s3 - a21
+            want = [a11, a21, s2, s3, s4, a22, s6]
+        for j in range(7):
+            assert np.array_equal(got[:, j], want[j]), (side, j)
+    # post-additions
+    Q = torch.from_numpy(np.stack([inputs.matrix(h, 80 + i, 1, "uniform") for i in range(live * 7)])).to(DEV)
+    hQ = Q.cpu().numpy().reshape(live, 7, h, h)
+    Cp = torch.full((live, n, n), float("nan"), dtype=torch.float64, device=DEV)
+    sw.sw_post_add(Q, h, h * h, live, h, Cp, n, n * n)
+    torch.cuda.synchronize()
+    got = Cp.cpu().numpy()
+    u1 = hQ[:, 0] + hQ[:, 3]; u2 = u1 + hQ[:, 4]; u3 = u1 + hQ[:, 2]
+    assert np.array_equal(q(got, 0, 0), hQ[:, 0] + hQ[:, 1])
+    assert np.array_equal(q(got, 0, 1), u3 + hQ[:, 5])
+    assert np.array_equal(q(got, 1, 0), u2 - hQ[:, 6])
+    assert np.array_equal(q(got, 1, 1), u2 + hQ[:, 2])
+
+
+def test_pad_copy_and_crop():
+    src = torch.from_numpy(inputs.matrix(37, 1, 0, "uniform")).to(DEV)
+    dst = torch.full((40, 48), float("nan"), dtype=torch.float64, device=DEV)
+    sw.sw_pad_copy(src, 37, 37, 37, dst, 48, 40, 40)
+    torch.cuda.synchronize()
+    d = dst.cpu().numpy()
+    assert np.array_equal(d[:37, :37], src.cpu().numpy())
+    assert (d[37:40, :40] == 0).all() and (d[:40, 37:40] == 0).all() and np.isnan(d[:, 40:]).all()
+    back = torch.empty((37, 37), dtype=torch.float64, device=DEV)
+    sw.sw_pad_copy(dst, 48, 40, 40, back, 37, 37, 37)
+    torch.cuda.synchronize()
+    assert torch.equal(back, src)
+
+
+# ---- the whole product against the oracle ---------------------------------------------------------------------------
+
+CASES = [
+    (256, 1, ["B", "D"], "uniform"),            # configuration 1
+    (64, 2, ["BB", "DD"], "uniform"),
+    (512, 2, ["BB", "BD", "DB", "DD"], "normal"),
+    (1000, 3, ["BBB", "DBD", "BDB", "DDD"], "rowscaled"),     # leaf 125: odd, several tiles, ragged
+    (1001, 3, ["DBB", "BDD"], "uniform"),                     # padded to 1008, leaf 126
+    (777, 2, ["BB", "DB"], "uniform"),                        # padded to 780, leaf 195
+    (2940, 2, ["DB", "BB"], "uniform"),                       # leaf 735 as in configuration 4
+    (96, 5, ["BDBDB", "DDDDD", "BBBBB"], "uniform"),          # leaf 3
+    (300, 0, [""], "uniform"),                                # no Strassen step at all
+    (1, 0, [""], "uniform"),
+]
+
+
+@pytest.mark.parametrize("n,levels,schedules,dist", CASES)
+def test_product_matches_oracle(oracle, n, levels, schedules, dist):
+    A = inputs.matrix(n, 1000 + n, 0, dist)
+    B = inputs.matrix(n, 1000 + n, 1, dist)
+    ref = oracle.gemm(A, B, levels)
+    first = None
+    for s in schedules:
+        C = run(A, B, levels, s)
+        err = float(np.max(np.abs(C - ref)))
+        assert err <= tol(n, A, B), (s, err)
+        if first is None:
+            first = C
+        else:
+            assert np.array_equal(C, first), f"result depends on the step order ({schedules[0]} vs {s})"
+    # integer-valued inputs: exact, equal to the oracle and to the integer product, whatever the order
+    Ai = inputs.matrix(n, 2000 + n, 0, "integer")
+    Bi = inputs.matrix(n, 2000 + n, 1, "integer")
+    exact = (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64)
+    assert np.array_equal(oracle.gemm(Ai, Bi, levels), exact)
+    for s in schedules:
+        assert np.array_equal(run(Ai, Bi, levels, s), exact), s
+
+
+def test_configuration_2_full_against_oracle(oracle):
+    cfg = inputs.CONFIGS[1]
+    n, levels = cfg["n"], cfg["levels"]
+    A, B = inputs.pair(cfg)
+    ref = oracle.gemm(A, B, levels)
+    C = run(A, B, levels, cfg["schedule"])
+    assert float(np.max(np.abs(C - ref))) <= tol(n, A, B)
+    assert np.array_equal(C, run(A, B, levels, "DBD"))
+
+
+def test_planner_choice_runs_and_library_state_calls(oracle):
+    n, levels = 640, 3
+    A = inputs.matrix(n, 5, 0, "uniform")
+    B = inputs.matrix(n, 5, 1, "uniform")
+    ref = oracle.gemm(A, B, levels)
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.empty_like(dA)
+    for budget, expect in [(sw.sw_plan_memory(n, levels, "DDD"), "DDD"), (sw.sw_plan_memory(n, levels, "DDB"), "DDB"),
+                           (10 ** 9, "BBB")]:
+        assert sw.sw_plan_schedule(n, levels, budget) == expect
+        ws = torch.empty(budget, dtype=torch.uint8, device=DEV)
+        sw.sw_set_workspace(ws)
+        sw.sw_set_stream(torch.cuda.current_stream().cuda_stream)
+        C.fill_(float("nan"))
+        sw.sw_gemm(n, dA, dB, C, levels, None)          # planner picks for this workspace
+        torch.cuda.synchronize()
+        assert float(np.max(np.abs(C.cpu().numpy() - ref))) <= tol(n, A, B)
+        sw.sw_set_workspace(None)
+    sw.sw_set_stream(0)
+
+
+def test_side_stream_and_profile_record(oracle):
+    n, levels = 512, 2
+    A = inputs.matrix(n, 8, 0, "uniform")
+    B = inputs.matrix(n, 8, 1, "uniform")
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.empty_like(dA)
+    ws = torch.empty(sw.sw_plan_memory(n, levels, "DB"), dtype=torch.uint8, device=DEV)
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    sw.sw_profile_enable(True)
+    with torch.cuda.stream(st):
+        sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, "DB", ws)
+    st.synchronize()
+    prof = sw.sw_profile_read()
+    sw.sw_profile_enable(False)
+    assert float(np.max(np.abs(C.cpu().numpy() - oracle.gemm(A, B, levels)))) <= tol(n, A, B)
+    assert prof["leaf_gemm"]["launches"] == 7 and prof["leaf_gemm"]["work"] == 49 * 2.0 * 128 ** 3
+    assert prof["pre_add"]["launches"] == 14 and prof["post_add"]["launches"] == 7
+    assert prof["dfs_add"]["launches"] == 8 and prof["pad"]["launches"] == 0
+    assert all(v["ms"] > 0 for k, v in prof.items() if v["launches"])
+
+
+def test_argument_errors_on_device():
+    n = 64
+    A = torch.zeros((n, n), dtype=torch.float64, device=DEV)
+    B = torch.zeros_like(A)
+    C = torch.zeros_like(A)
+    ws = torch.empty(sw.sw_plan_memory(n, 2, "BB"), dtype=torch.uint8, device=DEV)
+    cases = [
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, A, n, 2, "BB", ws), sw.SW_EINVAL),       # C aliases A
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 2, "B", ws), sw.SW_EINVAL),        # schedule too short
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 2, "BQ", ws), sw.SW_EINVAL),
+        (lambda: sw.sw_gemm_ex(n, A, n - 1, B, n, C, n, 2, "BB", ws), sw.SW_EINVAL),   # ld < n
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 7, "BBBBBBB", ws), sw.SW_EINVAL),  # 2^levels > n
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 2, "BB", ws[:1024]), sw.SW_ENOMEM),
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 2, "BB", None), sw.SW_ENOMEM),
+        (lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, 2, None, ws[:256]), sw.SW_ENOMEM),  # planner: nothing fits
+    ]
+    for call, code in cases:
+        with pytest.raises(sw.SwError) as e:
+            call()
+        assert e.value.code == code
+    # n = 0 is a no-op
+    Z = torch.zeros((0, 0), dtype=torch.float64, device=DEV)
+    assert sw.lib().sw_gemm_ex(0, None, 0, None, 0, None, 0, 0, b"", None, 0, None) == sw.SW_OK
+    assert Z.numel() == 0

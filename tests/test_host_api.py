@@ -1,0 +1,113 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared symbol, and the
+planner / memory / flop calls agree with the paper's formulas and with the oracle's tree walk."""
+import math
+import os
+import re
+
+import pytest
+
+from paper_1202_3173_amd import binding as sw
+from paper_1202_3173_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sw_gemm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sw_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(sw.EXPORTS)
+    L = sw.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_model_words_equals_oracle_tree_walk(oracle):
+    for n, levels, sched in [(256, 1, "B"), (4096, 3, "BBB"), (16384, 4, "DBBB"), (23520, 5, "BDBDB"),
+                             (94080, 5, "DDDBB"), (94080, 5, "DDDDD"), (64, 2, "DB"), (64, 2, "BD")]:
+        assert sw.sw_model_words(n, levels, sched) == oracle.peak_words(n, levels, sched) + 3 * n * n
+
+
+def test_model_words_closed_forms():
+    # Section 3.3.1: P * Mem_UM = 7 n^2 (7/4)^k - 4 n^2 ; Section 3.4.1: Mem_LM
+    n, k = 4096, 3
+    assert sw.sw_model_words(n, k, "BBB") == 7 * n * n * 7 ** k // 4 ** k - 4 * n * n
+    n, l, k = 94080, 3, 2
+    lm = sum(3 * n * n // 4 ** i for i in range(l)) + (7 * (n >> l) ** 2 * 7 ** k // 4 ** k - 4 * (n >> l) ** 2)
+    assert sw.sw_model_words(n, l + k, "DDDBB") == lm
+    # the survey's table of the paper-model footprint at n = 94080 (GB, incl. A, B, C)
+    for sched, gb in [("DDDDD", 283.16), ("DDDDB", 284.41), ("DDDBD", 289.39), ("DDDBB", 298.10)]:
+        assert sw.sw_model_words(94080, 5, sched) * 8 / 1e9 == pytest.approx(gb, abs=0.01)
+
+
+def test_flop_count_is_appendix_a_closed_form():
+    for cfg in inputs.CONFIGS:
+        n, L = cfg["n"], cfg["levels"]
+        n0 = n >> L
+        assert sw.sw_flop_count(n, L) == pytest.approx((2 * n0 + 4) * n0 * n0 * 7 ** L - 5 * n * n, rel=1e-14)
+    with pytest.raises(sw.SwError):
+        sw.sw_flop_count(100, 3)
+
+
+def test_plan_memory_structure():
+    # workspace really used: 21 half-size buffers per parent at a BFS step, 2 at a DFS step
+    def elems(h):
+        ld = (h + 15) // 16 * 16
+        if ld >= 256 and ld % 256 == 0:
+            ld += 16
+        return (ld * h + 31) // 32 * 32
+    assert sw.sw_plan_memory(256, 1, "B") == 21 * elems(128) * 8
+    assert sw.sw_plan_memory(256, 1, "D") == 2 * elems(128) * 8
+    assert sw.sw_plan_memory(1024, 2, "DB") == (2 * elems(512) + 21 * elems(256)) * 8
+    assert sw.sw_plan_memory(1024, 2, "BD") == (21 * elems(512) + 2 * 7 * elems(256)) * 8
+    assert sw.sw_plan_memory(1024, 2, None) == sw.sw_plan_memory(1024, 2, "DD")
+    assert sw.sw_plan_memory(1024, 0, "") == 0
+    # padding: 1001 -> 1008 with three padded copies
+    assert sw.sw_plan_memory(1001, 3, "DDD") == sw.sw_plan_memory(1008, 3, "DDD") + 3 * elems(1008) * 8
+    # never above the paper's model for the schedules used on the big configuration
+    assert sw.sw_plan_memory(94080, 5, "DDDBB") < (sw.sw_model_words(94080, 5, "DDDBB") - 3 * 94080 ** 2) * 8
+
+
+def test_planner_prefers_bfs_and_puts_dfs_first():
+    assert sw.sw_plan_schedule(4096, 3, 10 ** 11) == "BBB"
+    n, L = 94080, 5
+    gib288 = 288 * 2 ** 30 - 3 * n * n * 8          # what is left of 288 GiB beside A, B, C
+    s = sw.sw_plan_schedule(n, L, int(gib288 * 0.95))
+    assert s == "DDDBB"
+    assert sw.sw_plan_memory(n, L, s) <= gib288 * 0.95
+    assert sw.sw_plan_schedule(n, L, int(288e9 - 3 * n * n * 8)) == "DDDBB"
+    assert sw.sw_plan_schedule(n, L, int(50e9)) == "DDDDB"
+    assert sw.sw_plan_schedule(n, L, int(47.5e9)) == "DDDDD"
+    with pytest.raises(sw.SwError) as e:
+        sw.sw_plan_schedule(n, L, 10 ** 9)
+    assert e.value.code == sw.SW_ENOMEM
+    # every schedule the planner returns fits its budget; a bigger budget never gives fewer BFS steps
+    last = -1
+    for budget in [10 ** 8, 10 ** 9, 4 * 10 ** 9, 10 ** 10, 10 ** 11, 10 ** 12]:
+        s = sw.sw_plan_schedule(16384, 4, budget) if budget >= sw.sw_plan_memory(16384, 4, None) else None
+        if s is not None:
+            assert sw.sw_plan_memory(16384, 4, s) <= budget
+            assert s.count("B") >= last
+            last = s.count("B")
+            assert "BD" not in s            # DFS steps first (Limited-Memory shape)
+
+
+def test_lm_dfs_step_formula():
+    # l = max(0, ceil(log2(4 n / (P^(1/w0) sqrt(M)))))  (Section 3.4), checked inside its validity range
+    w0 = math.log2(7)
+    for n, P, M in [(94080, 49, 8e9 / 8), (94080, 343, 8e9 / 8), (94080, 2401, 8e9 / 8), (10 ** 6, 7, 1e9), (1000, 7, 1e9)]:
+        expect = max(0, math.ceil(math.log2(4 * n / (P ** (1 / w0) * math.sqrt(M)))))
+        assert sw.sw_lm_dfs_steps(n, P, M) == expect
+    assert sw.sw_lm_dfs_steps(1000, 7, 1e9) == 0
+    # the paper's own machine: n = 94080 on 49 nodes of 8 GB needs DFS steps, on 2401 nodes none
+    assert sw.sw_lm_dfs_steps(94080, 49, 1e9) > sw.sw_lm_dfs_steps(94080, 2401, 1e9) == 0
+
+
+def test_argument_errors_without_gpu():
+    for args in [(-1, 0, None), (16, -1, None), (16, 17, None), (4, 3, None), (16, 2, "B"), (16, 2, "BX"), (300000, 1, "B")]:
+        with pytest.raises(sw.SwError) as e:
+            sw.sw_plan_memory(*args)
+        assert e.value.code == sw.SW_EINVAL
+        assert sw.sw_last_error() != ""
+    with pytest.raises(sw.SwError):
+        sw.sw_model_words(100, 3, "BBB")
