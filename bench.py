@@ -1,0 +1,154 @@
+"""Benchmark of the Strassen-Winograd fp64 product on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5]
+
+A step is one whole product C = A*B (pre-additions, the BFS/DFS walk, batched leaf GEMMs, post-additions) on
+inputs already resident in HBM.  The default workload is the fifth configuration (n = 94080, five levels,
+step order chosen by the planner for the free device memory), the one the headline metric is quoted on:
+effective GFLOP/s = 2 n^3 / t (Section 5.2).  One JSON line is printed, with
+  roofline      the batched leaf GEMM (dominant kernel) against the fp64 matrix-core peak: actual flops
+                2 m^3 per leaf product, per launch, over the average launch time measured with HIP events
+                on the launch stream during the timed steps;
+  cpu_baseline  the CPU oracle timed on this host on one leaf-sized classical product and scaled through
+                the closed-form operation count (Appendix A) to the metric's unit.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FP64_MFMA_PEAK_TFLOPS = 78.6     # MI355X dense fp64 matrix peak (published)
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E peak (published)
+
+
+def cpu_baseline(n, levels):
+    """Oracle (as it stands, one thread) on one m x m classical leaf, m = n / 2^levels, scaled to the whole
+    product through F(n) = c_s n^w0 - 5 n^2: effective GFLOP/s = 2 n^3 / (F(n) / rate)."""
+    import importlib.util
+    import numpy as np
+    spec = importlib.util.spec_from_file_location("sw_oracle", os.path.join(ROOT, "oracle", "sw_oracle.py"))
+    sw_oracle = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(sw_oracle)
+    from paper_1202_3173_amd import binding, inputs
+    m = n >> levels
+    reps = 1
+    while reps * 2.0 * m ** 3 < 2e10 and reps < 4096:      # at least ~20 GFLOP of work for small leaves
+        reps *= 2
+    A = inputs.matrix(m, 99, 0, "uniform")
+    B = inputs.matrix(m, 99, 1, "uniform")
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        sw_oracle.gemm(A, B, 0)
+    dt = time.perf_counter() - t0
+    rate = reps * (2.0 * m ** 3 - m * m) / dt                # oracle's actual flop/s
+    total = binding.sw_flop_count(n, levels)
+    eff = 2.0 * n ** 3 / (total / rate) / 1e9
+    return {"value": round(eff, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": f"{reps} classical {m}x{m}x{m} leaf product(s) of the {7 ** levels} ({dt:.1f} s, "
+                      f"{rate / 1e9:.2f} actual GFLOP/s), scaled by the closed-form flop count F(n) of the "
+                      f"{levels}-level product"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default cfg5, the metric's configuration)")
+    ap.add_argument("--schedule", default=None, help="override the step order (default: the configuration's, or the planner's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1202_3173_amd import binding as sw
+    from paper_1202_3173_amd import inputs
+
+    cfg = next(c for c in inputs.CONFIGS if c["name"] == args.config)
+    n, levels = cfg["n"], cfg["levels"]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    A, B = inputs.device_pair(cfg, dev)
+    C = torch.empty((n, n), dtype=torch.float64, device=dev)
+    free, total_mem = torch.cuda.mem_get_info()
+    schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, int(free - (2 << 30)))
+    need = sw.sw_plan_memory(n, levels, schedule)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sw.sw_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = sw.sw_profile_read()
+    sw.sw_profile_enable(False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    eff_gflops = 2.0 * n ** 3 / (dt / args.steps) / 1e9
+
+    leaf = prof["leaf_gemm"]
+    leaf_tflops = leaf["work"] / (leaf["ms"] * 1e-3) / 1e12 if leaf["ms"] > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": "leaf_gemm_kernel (batched fp64 MFMA)",
+                "achieved": round(leaf_tflops, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(leaf_tflops / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "launches": leaf["launches"], "avg_launch_ms": round(leaf["ms"] / max(1, leaf["launches"]), 4),
+                "flops_per_launch": leaf["work"] / max(1, leaf["launches"])}
+    adds = {}
+    add_bytes = add_ms = 0.0
+    for k in ("pre_add", "post_add", "dfs_add", "pad"):
+        p = prof[k]
+        if p["launches"]:
+            adds[k] = {"GBps": round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1), "ms_per_step": round(p["ms"] / args.steps, 3),
+                       "launches_per_step": p["launches"] // args.steps}
+            add_bytes += p["work"]
+            add_ms += p["ms"]
+    add_gbps = add_bytes / (add_ms * 1e-3) / 1e9 if add_ms > 0 else 0.0
+
+    # cheap end-to-end sanity on the timed result (Freivalds, one +-1 vector, torch's own GEMV)
+    g = torch.Generator(device="cpu").manual_seed(1)
+    x = (torch.randint(0, 2, (n,), generator=g, dtype=torch.int64) * 2 - 1).to(torch.float64).to(dev)
+    check = float((torch.mv(C, x) - torch.mv(A, torch.mv(B, x))).abs().max())
+    absmax = lambda t: max(float(t[r:r + 4096].abs().max()) for r in range(0, n, 4096))   # chunked: no n x n temporary
+    tol = 1e-10 * n * absmax(A) * absmax(B)
+
+    out = {
+        "metric": "effective fp64 GFLOP/s (2n^3/t)", "value": round(eff_gflops, 1), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: n={n} square fp64 C=A*B, {levels} Strassen-Winograd levels, "
+                               f"leaf {n >> levels}, entries {cfg['dist']} seed {cfg['seed']}",
+                   "n": n, "levels": levels, "schedule": schedule, "workspace_GB": round(need / 1e9, 3),
+                   "hbm_total_GB": round(total_mem / 1e9, 1)},
+        "pct_of_fp64_mfma_peak": round(100.0 * eff_gflops / (FP64_MFMA_PEAK_TFLOPS * 1e3), 2),
+        "actual_flops_per_step": sw.sw_flop_count(n, levels),
+        "roofline": roofline,
+        "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
+                      "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds},
+        "leaf_ms_per_step": round(leaf["ms"] / args.steps, 3),
+        "check": {"freivalds_max_abs_diff": check, "tolerance": tol, "ok": check <= tol},
+        "paper_context": "Cray XT4: 49.1 effective GFLOPS/node, 33% above the classical peak (Section 5.2)",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(n, levels)
+    print(json.dumps(out))
+    if check > tol:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()
