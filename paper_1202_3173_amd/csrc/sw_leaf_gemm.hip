@@ -3,24 +3,27 @@
 //
 //   C_b = A_b * B_b,  b < batch, every matrix m x m, row-major, one launch for the whole batch.
 //
-// Design (gfx950, 256 CUs, 64-wide wavefronts, v_mfma_f64_16x16x4_f64):
+// Design (gfx950, 256 CUs, 64-wide wavefronts, v_mfma_f64_16x16x4_f64 = 64 cycles of one SIMD's matrix pipe):
 //   * a workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128 tile of one C_b; each wavefront owns
 //     64 x 64 of it as 4 x 4 MFMA tiles of 16 x 16, i.e. 64 fp64 accumulators per lane, kept in VGPRs;
-//   * K is walked in slabs of 16; a slab of A (128 x 16) and of B (16 x 128) is loaded from global memory
-//     into registers while the previous slab is being multiplied, then written to the other half of a
-//     double-buffered LDS area: one barrier per slab;
-//   * LDS layouts make every fragment read one conflict-free ds_read_b128 that feeds TWO MFMAs: A is kept
-//     [row][k] with a row pitch of 18 doubles, B is kept [k/2][col][k%2] so that the two k of a pair sit side
-//     by side.  The MFMA of lane group g (= lane / 16) may use any k as long as A and B agree, so group g
-//     takes k = 8q + 2g and 8q + 2g + 1 (q = 0, 1) of the slab for its two consecutive MFMAs;
-//   * two workgroups fit per CU (70 KB of LDS each, < 256 VGPRs), so one wavefront's barrier or LDS wait is
-//     covered by the other's MFMAs;
+//   * K is walked in slabs of 16 = four MFMA k-steps.  Per slab a wavefront issues 64 MFMAs; everything else
+//     is threaded between them so the matrix pipe never waits on it:
+//       k-step 0: write the NEXT slab (loaded from global memory one slab earlier) into the other LDS buffer
+//       k-step 1: issue the global loads of the slab after that into the freed staging registers
+//       k-steps 0..2: read the fragments of the following k-step from LDS into the other fragment set
+//       one barrier, then k-step 3 runs while the first fragments of the next slab are read;
+//   * LDS: A slab as [row][k] with a pitch of 18 doubles, B slab as [k][col] with a pitch of 144 doubles;
+//     with these pitches the 8-byte fragment reads of 32 consecutive lanes fall on 32 distinct bank pairs;
+//   * two workgroups fit per CU (72 KB of LDS each, < 256 VGPRs), so what one wavefront cannot hide (the
+//     barrier itself) is covered by the other workgroup's MFMAs;
 //   * workgroup ids are remapped so that each XCD (ids congruent mod 8 share an XCD and its L2) works on a
 //     contiguous run of tiles, ordered in groups of 8 tile rows: the ~64 tiles in flight on an XCD then
 //     share A row panels and B column panels through that L2;
-//   * edges (m not a multiple of 128, K not a multiple of 16) are handled by zero-filled loads and
-//     bounds-checked stores; 16-byte global loads are used when pointers, leading dimensions and m allow
-//     it, 8-byte loads otherwise.
+//   * edges: rows and columns beyond m are clamped to the last valid one on load (their products land in
+//     accumulators that are never stored); the K tail is zero-filled; stores are bounds-checked.  16-byte
+//     global loads when pointers, leading dimensions and m allow it, 8-byte loads otherwise.
+#include <type_traits>
+
 #include "sw_internal.h"
 
 namespace sw {
@@ -30,10 +33,10 @@ typedef double v2d __attribute__((ext_vector_type(2)));
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 16, NT = 256;
-constexpr int SA = 18;                 // LDS pitch of an A row (doubles): 16 + 2 keeps b128 reads conflict-free
-constexpr int SBP = 2 * BN + 4;        // LDS pitch of a B k-pair row (doubles)
+constexpr int SA = 18;                 // LDS pitch of an A row (doubles)
+constexpr int SB = BN + 16;            // LDS pitch of a B k-row (doubles)
 constexpr int A_ELEMS = BM * SA;       // 2304
-constexpr int B_ELEMS = (BK / 2) * SBP;  // 2080
+constexpr int B_ELEMS = BK * SB;       // 2304
 constexpr int STAGE = A_ELEMS + B_ELEMS;
 constexpr int GROUP_M = 8;             // tile rows per ordering group
 constexpr int NUM_XCD = 8;
@@ -54,7 +57,7 @@ leaf_gemm_kernel(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) double smem[2 * STAGE];
 
-    // ---- which tile: XCD-aware remap, then grouped row-major order inside a matrix ----
+    // ---- which tile: XCD-aware remap, then grouped order inside a matrix ----
     const int nb = gridDim.x;
     const int bid = blockIdx.x;
     const int xcd = bid % NUM_XCD;
@@ -71,8 +74,9 @@ leaf_gemm_kernel(const GemmArgs g)
     const int tile_n = tin / gsz;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const double* __restrict__ A = g.A + (int64_t)batch * g.sa;
-    const double* __restrict__ B = g.B + (int64_t)batch * g.sb;
+    // uniform bases of this tile's A row panel and B column panel
+    const double* __restrict__ A = g.A + (int64_t)batch * g.sa + (int64_t)m0 * g.lda;
+    const double* __restrict__ B = g.B + (int64_t)batch * g.sb + n0;
     double* __restrict__ C = g.C + (int64_t)batch * g.sc;
 
     const int tid = threadIdx.x;
@@ -80,106 +84,168 @@ leaf_gemm_kernel(const GemmArgs g)
     const int r16 = lane & 15, g4 = lane >> 4;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- global -> register staging -------------------------------------------------------------------
-    // VEC == 2: A: 4 loads of 2 doubles: row tid/8 + 32 i, k (tid%8)*2.   B: k pair tid/64 + 4 i (i < 2),
-    //           columns (tid%64)*2, +1; the two k of the pair are two loads.
-    // VEC == 1: A: 8 loads: row tid/16 + 16 i, k tid%16.                  B: k pair tid/128 + 2 i (i < 4),
-    //           column tid%128.
-    constexpr int NA = VEC == 2 ? 4 : 8;
-    constexpr int NBP = VEC == 2 ? 2 : 4;
+    // ---- global -> register staging: who loads what --------------------------------------------------------
+    // VEC == 2: A: row tid/8 + 32 i (i < 4), k (tid%8)*2, +1.        B: k tid/64 + 4 i (i < 4), cols (tid%64)*2, +1
+    // VEC == 1: A: row tid/16 + 16 i (i < 8), k tid%16.              B: k tid/128 + 2 i (i < 8), col tid%128
+    typedef typename std::conditional<VEC == 2, v2d, double>::type V;
+    constexpr int NL = VEC == 2 ? 4 : 8;
+    constexpr int A_RSTEP = VEC == 2 ? 32 : 16;
+    constexpr int B_KSTEP = VEC == 2 ? 4 : 2;
     const int a_k = VEC == 2 ? (tid & 7) * 2 : (tid & 15);
     const int a_r0 = VEC == 2 ? (tid >> 3) : (tid >> 4);
-    constexpr int A_RSTEP = VEC == 2 ? 32 : 16;
     const int b_c = VEC == 2 ? (tid & 63) * 2 : (tid & 127);
-    const int b_p0 = VEC == 2 ? (tid >> 6) : (tid >> 7);
-    constexpr int B_PSTEP = VEC == 2 ? 4 : 2;
+    const int b_k0 = VEC == 2 ? (tid >> 6) : (tid >> 7);
 
-    typedef typename std::conditional<VEC == 2, v2d, double>::type V;
-    V ra[NA];
-    V rb[NBP][2];
+    // element offsets from the uniform panel bases (rows / columns clamped into the matrix); they stay
+    // below 128 * ld, so 32 bits are enough whatever the matrix size
+    unsigned offA[NL], offB[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int row = min(a_r0 + i * A_RSTEP, g.M - 1 - m0);
+        offA[i] = (unsigned)((int64_t)row * g.lda) + (unsigned)a_k;
+        offB[i] = (unsigned)((int64_t)(b_k0 + i * B_KSTEP) * g.ldb) + (unsigned)min(b_c, g.N - VEC - n0);
+    }
 
-    const bool b_col_ok = n0 + b_c < g.N;   // VEC == 2 requires N even, so the pair is in or out together
+    V ra[NL], rb[NL];
 
-    auto gload = [&](int k0) {
+    // slab starting at k0; TAIL: the slab reaches beyond K, so k is clamped for the address and zero-filled
+    auto gload = [&](int k0, auto tail) __attribute__((always_inline)) {
+        constexpr bool TAIL = decltype(tail)::value;
+        const double* __restrict__ As = A + k0;
+        const double* __restrict__ Bs = B + (int64_t)k0 * g.ldb;
+        if constexpr (!TAIL) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int row = m0 + a_r0 + i * A_RSTEP;
-            const int k = k0 + a_k;
-            V v = V(0.0);
-            if (row < g.M && k < g.K) v = *reinterpret_cast<const V*>(A + (int64_t)row * g.lda + k);
-            ra[i] = v;
-        }
+            for (int i = 0; i < NL; ++i) ra[i] = *reinterpret_cast<const V*>(As + offA[i]);
 #pragma unroll
-        for (int i = 0; i < NBP; ++i) {
+            for (int i = 0; i < NL; ++i) rb[i] = *reinterpret_cast<const V*>(Bs + offB[i]);
+        } else {
+            const bool a_ok = k0 + a_k < g.K;                       // VEC == 2: K even, the pair is in or out
+            const int a_back = a_ok ? 0 : (k0 + a_k) - (g.K - VEC);  // step back inside the row
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int k = k0 + 2 * (b_p0 + i * B_PSTEP) + e;
-                V v = V(0.0);
-                if (b_col_ok && k < g.K) v = *reinterpret_cast<const V*>(B + (int64_t)k * g.ldb + n0 + b_c);
-                rb[i][e] = v;
+            for (int i = 0; i < NL; ++i) {
+                const V v = *reinterpret_cast<const V*>(As + ((int64_t)offA[i] - a_back));
+                ra[i] = a_ok ? v : V(0.0);
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int k = k0 + b_k0 + i * B_KSTEP;
+                const bool ok = k < g.K;
+                const int64_t back = ok ? 0 : (int64_t)(k - (g.K - 1)) * g.ldb;
+                const V v = *reinterpret_cast<const V*>(Bs + ((int64_t)offB[i] - back));
+                rb[i] = ok ? v : V(0.0);
             }
         }
     };
 
-    auto sstore = [&](int buf) {
+    auto sstore_a = [&](int buf) __attribute__((always_inline)) {
         double* As = smem + buf * STAGE;
-        double* Bs = As + A_ELEMS;
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
-            *reinterpret_cast<V*>(As + (a_r0 + i * A_RSTEP) * SA + a_k) = ra[i];
-#pragma unroll
-        for (int i = 0; i < NBP; ++i) {
-            double* dst = Bs + (b_p0 + i * B_PSTEP) * SBP + b_c * 2;
-            if constexpr (VEC == 2) {
-                v2d lo = {rb[i][0][0], rb[i][1][0]};
-                v2d hi = {rb[i][0][1], rb[i][1][1]};
-                *reinterpret_cast<v2d*>(dst) = lo;
-                *reinterpret_cast<v2d*>(dst + 2) = hi;
-            } else {
-                v2d p = {rb[i][0], rb[i][1]};
-                *reinterpret_cast<v2d*>(dst) = p;
-            }
-        }
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<V*>(As + (a_r0 + i * A_RSTEP) * SA + a_k) = ra[i];
     };
+    auto sstore_b = [&](int buf) __attribute__((always_inline)) {
+        double* Bs = smem + buf * STAGE + A_ELEMS;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<V*>(Bs + (b_k0 + i * B_KSTEP) * SB + b_c) = rb[i];
+    };
+    auto sstore = [&](int buf) __attribute__((always_inline)) { sstore_a(buf); sstore_b(buf); };
 
+    // ---- fragments and accumulators -------------------------------------------------------------------------
     v4d acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
 
-    auto compute = [&](int buf) {
-        const double* As = smem + buf * STAGE + (wm * 64 + r16) * SA + 2 * g4;
-        const double* Bs = smem + buf * STAGE + A_ELEMS + g4 * SBP + (wn * 64 + r16) * 2;
+    double fa[2][4], fb[2][4];   // two fragment sets: one feeds the MFMAs while the other is being read
+
+    // k-step s of the slab in buffer buf: lane (r16, g4) holds A[16 i + r16][4 s + g4] and B[4 s + g4][16 j + r16]
+    auto fread = [&](int buf, int s, int set) __attribute__((always_inline)) {
+        const double* As = smem + buf * STAGE + (wm * 64 + r16) * SA + 4 * s + g4;
+        const double* Bs = smem + buf * STAGE + A_ELEMS + (4 * s + g4) * SB + wn * 64 + r16;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            v2d a[4], b[4];
+        for (int i = 0; i < 4; ++i) fa[set][i] = As[i * 16 * SA];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const v2d*>(As + i * 16 * SA + 8 * q);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const v2d*>(Bs + 4 * q * SBP + j * 32);
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i][e], b[j][e], acc[i][j], 0, 0, 0);
-        }
+        for (int j = 0; j < 4; ++j) fb[set][j] = Bs[j * 16];
     };
 
+    // MFMA tile rows i0 .. i1-1 of one k-step
+    auto mfma_rows = [&](int set, int i0, int i1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+#define SW_FENCE() __builtin_amdgcn_sched_barrier(0)
+
     const int KT = (g.K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
+    const bool ragged = (g.K % BK) != 0;     // only the last slab can reach beyond K
+
+    // One slab.  STORE: the next slab is in the staging registers and goes to the other LDS buffer.
+    // LOAD: 0 nothing, 1 start the plain global loads of slab kt + 2, 2 the same with the K tail zero-filled.
+    // The steady state (STORE, LOAD == 1) is straight-line code; the last three slabs are peeled below.
+    auto slab = [&](int kt, auto store_c, auto load_c) __attribute__((always_inline)) {
+        constexpr bool STORE = decltype(store_c)::value;
+        constexpr int LOAD = decltype(load_c)::value;
         const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) gload((kt + 1) * BK);
-        compute(cur);
-        if (more) sstore(cur ^ 1);
+        // The scheduling fences pin the order written here: LDS reads for the NEXT k-step are issued before
+        // the MFMAs of this one, and stores / global loads are slipped between groups of four MFMAs, whose
+        // 256 cycles of matrix-pipe time cover their issue.
+        // k-step 0: fetch the fragments of k-step 1, publish the next slab
+        fread(cur, 1, 1);
+        SW_FENCE();
+        mfma_rows(0, 0, 1);
+        SW_FENCE();
+        if constexpr (STORE) sstore_a(cur ^ 1);
+        SW_FENCE();
+        mfma_rows(0, 1, 2);
+        SW_FENCE();
+        if constexpr (STORE) sstore_b(cur ^ 1);
+        SW_FENCE();
+        mfma_rows(0, 2, 4);
+        SW_FENCE();
+        // k-step 1: start the global loads of the slab after next into the freed staging registers
+        fread(cur, 2, 0);
+        SW_FENCE();
+        mfma_rows(1, 0, 1);
+        SW_FENCE();
+        if constexpr (LOAD == 1) gload((kt + 2) * BK, std::false_type{});
+        if constexpr (LOAD == 2) gload((kt + 2) * BK, std::true_type{});
+        SW_FENCE();
+        mfma_rows(1, 1, 4);
+        SW_FENCE();
+        // k-step 2
+        fread(cur, 3, 1);
+        SW_FENCE();
+        mfma_rows(0, 0, 4);
+        SW_FENCE();
+        // every wavefront has stored the next slab and finished reading this one
         __syncthreads();
+        // k-step 3, overlapped with the first fragment reads of the next slab
+        if constexpr (STORE) fread(cur ^ 1, 0, 0);
+        SW_FENCE();
+        mfma_rows(1, 0, 4);
+        SW_FENCE();
+    };
+    using std::integral_constant;
+    typedef integral_constant<bool, true> Yes;
+    typedef integral_constant<bool, false> No;
+
+    if (KT == 1 && ragged) gload(0, std::true_type{}); else gload(0, std::false_type{});
+    sstore(0);
+    if (KT > 1) { if (KT == 2 && ragged) gload(BK, std::true_type{}); else gload(BK, std::false_type{}); }
+    __syncthreads();
+    fread(0, 0, 0);
+
+    int kt = 0;
+    for (; kt + 3 < KT; ++kt) slab(kt, Yes{}, integral_constant<int, 1>{});      // slab kt + 2 is not the last
+    if (kt + 2 < KT) {                                                            // slab kt + 2 is the last one
+        if (ragged) slab(kt, Yes{}, integral_constant<int, 2>{});
+        else slab(kt, Yes{}, integral_constant<int, 1>{});
+        ++kt;
     }
+    if (kt + 1 < KT) { slab(kt, Yes{}, integral_constant<int, 0>{}); ++kt; }
+    slab(kt, No{}, integral_constant<int, 0>{});
 
     // ---- store: accumulator v of lane (r16, g4) in MFMA tile (i, j) is C[16 i + g4 + 4 v][16 j + r16] ----
 #pragma unroll
@@ -204,6 +270,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s)
 {
     if (m == 0 || batch == 0) return hipSuccess;
+    // per-thread offsets inside one 128-row panel / 16-row slab are 32-bit element counts
+    if (128 * a.ld >= (int64_t)1 << 31 || 16 * b.ld >= (int64_t)1 << 31) return hipErrorInvalidValue;
     GemmArgs g;
     g.A = a.p; g.B = b.p; g.C = c.p;
     g.lda = a.ld; g.ldb = b.ld; g.ldc = c.ld;
