@@ -5,7 +5,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsw_gemm.so")
+LIB_PATH = os.environ.get("SW_GEMM_LIB") or os.path.join(_HERE, "libsw_gemm.so")   # override: a library built elsewhere
 
 SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
 SW_MAX_LEVELS = 16

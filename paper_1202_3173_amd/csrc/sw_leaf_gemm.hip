@@ -38,7 +38,10 @@ constexpr int SB = BN + 16;            // LDS pitch of a B k-row (doubles)
 constexpr int A_ELEMS = BM * SA;       // 2304
 constexpr int B_ELEMS = BK * SB;       // 2304
 constexpr int STAGE = A_ELEMS + B_ELEMS;
-constexpr int GROUP_M = 8;             // tile rows per ordering group
+#ifndef SW_GROUP_M
+#define SW_GROUP_M 8
+#endif
+constexpr int GROUP_M = SW_GROUP_M;    // tile rows per ordering group
 constexpr int NUM_XCD = 8;
 
 struct GemmArgs {
@@ -62,7 +65,11 @@ leaf_gemm_kernel(const GemmArgs g)
     const int bid = blockIdx.x;
     const int xcd = bid % NUM_XCD;
     const int per = nb / NUM_XCD, rem = nb % NUM_XCD;
+#ifdef SW_NO_XCD_REMAP
+    const int logical = bid; (void)xcd; (void)per; (void)rem;
+#else
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + bid / NUM_XCD;
+#endif
     const int tpm = g.tiles_m * g.tiles_n;
     const int batch = logical / tpm;
     const int t = logical - batch * tpm;
@@ -96,44 +103,51 @@ leaf_gemm_kernel(const GemmArgs g)
     const int b_c = VEC == 2 ? (tid & 63) * 2 : (tid & 127);
     const int b_k0 = VEC == 2 ? (tid >> 6) : (tid >> 7);
 
-    // element offsets from the uniform panel bases (rows / columns clamped into the matrix); they stay
-    // below 128 * ld, so 32 bits are enough whatever the matrix size
+    // BYTE offsets from the uniform panel bases (rows / columns clamped into the matrix).  They stay below
+    // 128 * ld * 8 < 2^32, so every load is "uniform 64-bit base in SGPRs + 32-bit per-lane offset" and
+    // the K loop advances the bases with scalar adds only: no vector ALU work competes with the MFMAs.
     unsigned offA[NL], offB[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
         const int row = min(a_r0 + i * A_RSTEP, g.M - 1 - m0);
-        offA[i] = (unsigned)((int64_t)row * g.lda) + (unsigned)a_k;
-        offB[i] = (unsigned)((int64_t)(b_k0 + i * B_KSTEP) * g.ldb) + (unsigned)min(b_c, g.N - VEC - n0);
+        offA[i] = ((unsigned)((int64_t)row * g.lda) + (unsigned)a_k) * 8u;
+        offB[i] = ((unsigned)((int64_t)(b_k0 + i * B_KSTEP) * g.ldb) + (unsigned)min(b_c, g.N - VEC - n0)) * 8u;
     }
 
     V ra[NL], rb[NL];
 
-    // slab starting at k0; TAIL: the slab reaches beyond K, so k is clamped for the address and zero-filled
-    auto gload = [&](int k0, auto tail) __attribute__((always_inline)) {
-        constexpr bool TAIL = decltype(tail)::value;
-        const double* __restrict__ As = A + k0;
-        const double* __restrict__ Bs = B + (int64_t)k0 * g.ldb;
-        if constexpr (!TAIL) {
+    // a whole slab whose uniform byte bases are pa (A panel at column k0) and pb (B panel at row k0)
+    auto gload = [&](const char* __restrict__ pa, const char* __restrict__ pb) __attribute__((always_inline)) {
+        // The empty asm keeps each 32-bit offset opaque inside the loop, so that instruction selection
+        // sees "scalar base + zero-extended 32-bit lane offset" and emits the SGPR-base form of global_load
+        // instead of a 64-bit vector add per load.
 #pragma unroll
-            for (int i = 0; i < NL; ++i) ra[i] = *reinterpret_cast<const V*>(As + offA[i]);
+        for (int i = 0; i < NL; ++i) {
+            asm volatile("" : "+v"(offA[i]));
+            ra[i] = *reinterpret_cast<const V*>(pa + offA[i]);
+        }
 #pragma unroll
-            for (int i = 0; i < NL; ++i) rb[i] = *reinterpret_cast<const V*>(Bs + offB[i]);
-        } else {
-            const bool a_ok = k0 + a_k < g.K;                       // VEC == 2: K even, the pair is in or out
-            const int a_back = a_ok ? 0 : (k0 + a_k) - (g.K - VEC);  // step back inside the row
+        for (int i = 0; i < NL; ++i) {
+            asm volatile("" : "+v"(offB[i]));
+            rb[i] = *reinterpret_cast<const V*>(pb + offB[i]);
+        }
+    };
+    // the last slab when it reaches beyond K: k is clamped for the address and the value zero-filled
+    auto gload_tail = [&](int k0) __attribute__((always_inline)) {
+        const bool a_ok = k0 + a_k < g.K;                            // VEC == 2: K even, the pair is in or out
+        const int a_back = a_ok ? 0 : ((k0 + a_k) - (g.K - VEC)) * 8;  // bytes to step back inside the row
 #pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                const V v = *reinterpret_cast<const V*>(As + ((int64_t)offA[i] - a_back));
-                ra[i] = a_ok ? v : V(0.0);
-            }
+        for (int i = 0; i < NL; ++i) {
+            const V v = *reinterpret_cast<const V*>(reinterpret_cast<const char*>(A + k0) + ((int64_t)offA[i] - a_back));
+            ra[i] = a_ok ? v : V(0.0);
+        }
 #pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                const int k = k0 + b_k0 + i * B_KSTEP;
-                const bool ok = k < g.K;
-                const int64_t back = ok ? 0 : (int64_t)(k - (g.K - 1)) * g.ldb;
-                const V v = *reinterpret_cast<const V*>(Bs + ((int64_t)offB[i] - back));
-                rb[i] = ok ? v : V(0.0);
-            }
+        for (int i = 0; i < NL; ++i) {
+            const int k = k0 + b_k0 + i * B_KSTEP;
+            const bool ok = k < g.K;
+            const int64_t back = ok ? 0 : (int64_t)(k - (g.K - 1)) * g.ldb * 8;
+            const V v = *reinterpret_cast<const V*>(reinterpret_cast<const char*>(B + (int64_t)k0 * g.ldb) + ((int64_t)offB[i] - back));
+            rb[i] = ok ? v : V(0.0);
         }
     };
 
@@ -170,37 +184,42 @@ leaf_gemm_kernel(const GemmArgs g)
 
     // MFMA tile rows i0 .. i1-1 of one k-step
     auto mfma_rows = [&](int set, int i0, int i1) __attribute__((always_inline)) {
+#ifdef SW_SETPRIO
+        __builtin_amdgcn_s_setprio(1);
+#endif
 #pragma unroll
         for (int i = i0; i < i1; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+#ifdef SW_SETPRIO
+        __builtin_amdgcn_s_setprio(0);
+#endif
     };
 #define SW_FENCE() __builtin_amdgcn_sched_barrier(0)
 
     const int KT = (g.K + BK - 1) / BK;
     const bool ragged = (g.K % BK) != 0;     // only the last slab can reach beyond K
+    const int64_t stepA = (int64_t)BK * 8, stepB = (int64_t)BK * g.ldb * 8;
+    const char* pa = reinterpret_cast<const char*>(A);   // uniform bases of the NEXT slab to load
+    const char* pb = reinterpret_cast<const char*>(B);
 
-    // One slab.  STORE: the next slab is in the staging registers and goes to the other LDS buffer.
-    // LOAD: 0 nothing, 1 start the plain global loads of slab kt + 2, 2 the same with the K tail zero-filled.
-    // The steady state (STORE, LOAD == 1) is straight-line code; the last three slabs are peeled below.
-    auto slab = [&](int kt, auto store_c, auto load_c) __attribute__((always_inline)) {
-        constexpr bool STORE = decltype(store_c)::value;
-        constexpr int LOAD = decltype(load_c)::value;
-        const int cur = kt & 1;
-        // The scheduling fences pin the order written here: LDS reads for the NEXT k-step are issued before
-        // the MFMAs of this one, and stores / global loads are slipped between groups of four MFMAs, whose
-        // 256 cycles of matrix-pipe time cover their issue.
+    // One slab held in LDS buffer `cur`.  The scheduling fences pin the order written here: LDS reads for
+    // the NEXT k-step are issued before the MFMAs of this one, and stores / global loads are slipped
+    // between groups of four MFMAs, whose 256 cycles of matrix-pipe time cover their issue.
+    //   store: the next slab is in the staging registers and goes to the other buffer
+    //   load:  0 nothing, 1 start the global loads of the slab after next, 2 the same, zero-filling the K tail
+    auto slab = [&](int kt, int cur, bool store, int load) __attribute__((always_inline)) {
         // k-step 0: fetch the fragments of k-step 1, publish the next slab
         fread(cur, 1, 1);
         SW_FENCE();
         mfma_rows(0, 0, 1);
         SW_FENCE();
-        if constexpr (STORE) sstore_a(cur ^ 1);
+        if (store) sstore_a(cur ^ 1);
         SW_FENCE();
         mfma_rows(0, 1, 2);
         SW_FENCE();
-        if constexpr (STORE) sstore_b(cur ^ 1);
+        if (store) sstore_b(cur ^ 1);
         SW_FENCE();
         mfma_rows(0, 2, 4);
         SW_FENCE();
@@ -209,8 +228,10 @@ leaf_gemm_kernel(const GemmArgs g)
         SW_FENCE();
         mfma_rows(1, 0, 1);
         SW_FENCE();
-        if constexpr (LOAD == 1) gload((kt + 2) * BK, std::false_type{});
-        if constexpr (LOAD == 2) gload((kt + 2) * BK, std::true_type{});
+#ifndef SW_EXP_NOLOAD   /* timing experiment only: results are wrong without the loads */
+        if (load == 1) { gload(pa, pb); pa += stepA; pb += stepB; }
+        if (load == 2) gload_tail((kt + 2) * BK);
+#endif
         SW_FENCE();
         mfma_rows(1, 1, 4);
         SW_FENCE();
@@ -220,32 +241,35 @@ leaf_gemm_kernel(const GemmArgs g)
         mfma_rows(0, 0, 4);
         SW_FENCE();
         // every wavefront has stored the next slab and finished reading this one
+#ifndef SW_EXP_NOBARRIER   /* timing experiment only: LDS contents race without it (addresses stay in bounds) */
         __syncthreads();
+#endif
         // k-step 3, overlapped with the first fragment reads of the next slab
-        if constexpr (STORE) fread(cur ^ 1, 0, 0);
+        if (store) fread(cur ^ 1, 0, 0);
         SW_FENCE();
         mfma_rows(1, 0, 4);
         SW_FENCE();
     };
-    using std::integral_constant;
-    typedef integral_constant<bool, true> Yes;
-    typedef integral_constant<bool, false> No;
 
-    if (KT == 1 && ragged) gload(0, std::true_type{}); else gload(0, std::false_type{});
+    if (KT == 1 && ragged) gload_tail(0); else { gload(pa, pb); pa += stepA; pb += stepB; }
     sstore(0);
-    if (KT > 1) { if (KT == 2 && ragged) gload(BK, std::true_type{}); else gload(BK, std::false_type{}); }
+    if (KT > 1) { if (KT == 2 && ragged) gload_tail(BK); else { gload(pa, pb); pa += stepA; pb += stepB; } }
     __syncthreads();
     fread(0, 0, 0);
 
+    // steady state, two slabs per trip so that the LDS buffer index is a compile-time constant and all
+    // LDS addresses are "per-lane base + immediate": straight-line code without vector ALU instructions
     int kt = 0;
-    for (; kt + 3 < KT; ++kt) slab(kt, Yes{}, integral_constant<int, 1>{});      // slab kt + 2 is not the last
-    if (kt + 2 < KT) {                                                            // slab kt + 2 is the last one
-        if (ragged) slab(kt, Yes{}, integral_constant<int, 2>{});
-        else slab(kt, Yes{}, integral_constant<int, 1>{});
-        ++kt;
+    for (; kt + 4 < KT; kt += 2) {
+        slab(kt, 0, true, 1);
+        slab(kt + 1, 1, true, 1);
     }
-    if (kt + 1 < KT) { slab(kt, Yes{}, integral_constant<int, 0>{}); ++kt; }
-    slab(kt, No{}, integral_constant<int, 0>{});
+    // the last (up to four) slabs: nothing more to store or load at the very end, and a ragged K tail
+    for (; kt < KT; ++kt) {
+        const bool store = kt + 1 < KT;
+        const int load = kt + 2 < KT ? ((ragged && kt + 2 == KT - 1) ? 2 : 1) : 0;
+        slab(kt, kt & 1, store, load);
+    }
 
     // ---- store: accumulator v of lane (r16, g4) in MFMA tile (i, j) is C[16 i + g4 + 4 v][16 j + r16] ----
 #pragma unroll
