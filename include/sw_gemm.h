@@ -55,8 +55,9 @@ int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t
 /* ---- the planner (Section 3.1: pick the step order that uses the memory there is; Sections 3.3.1, 3.4.1) - */
 
 /* Bytes of workspace sw_gemm needs beyond A, B, C for this n, depth and step order (what THIS library
- * allocates from the workspace: 21 half-size buffers per parent at a BFS step, 2 at a DFS step, padded
- * leading dimensions, plus padded copies of A, B, C when 2^levels does not divide n).  schedule NULL or "":
+ * allocates from the workspace: 21 half-size buffers per parent at a BFS step -- or 147 quarter-size ones for
+ * two fused BFS steps --, 2 at a DFS step, padded leading dimensions, plus padded copies of A, B, C when
+ * 2^levels does not divide n).  schedule NULL or "":
  * the all-DFS order (the minimum).  Pure host arithmetic; needs no GPU.  Negative = error code. */
 int64_t sw_plan_memory(int64_t n, int levels, const char* schedule);
 
@@ -99,6 +100,15 @@ int sw_pre_add(int side, const double* parent, int64_t parent_ld, int64_t parent
  * C11 = Q0+Q1, C12 = U3+Q5, C21 = U2-Q6, C22 = U2+Q2, in this association, for `live` parents. */
 int sw_post_add(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, int64_t h,
                 double* parent, int64_t parent_ld, int64_t parent_stride, void* hip_stream);
+
+/* Two consecutive BFS steps in one pass (what sw_gemm uses when the step order has "BB"): each parent
+ * (4m x 4m) gives the operands of its 49 grandchildren (m x m), grandchild (j, i) = T_i of (T_j of the
+ * parent), stored at child + (49 p + 7 j + i) * child_stride; the values are bit-identical to two sw_pre_add
+ * calls, the 28 intermediate blocks never reach memory.  sw_post_add2 is the reverse for the products. */
+int sw_pre_add2(int side, const double* parent, int64_t parent_ld, int64_t parent_stride, int64_t live,
+                int64_t m, double* child, int64_t child_ld, int64_t child_stride, void* hip_stream);
+int sw_post_add2(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, int64_t m,
+                 double* parent, int64_t parent_ld, int64_t parent_stride, void* hip_stream);
 
 /* Classical leaf products (Section 5.4.1): C_b = A_b * B_b for b < batch, each m x m, fp64 MFMA
  * (v_mfma_f64_16x16x4_f64), one launch for the whole batch.  Operand b starts at base + b*stride. */

@@ -13,7 +13,7 @@ CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad")
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_last_error", "sw_pre_add", "sw_post_add",
-           "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
+           "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
 
 
 class SwError(RuntimeError):
@@ -47,6 +47,8 @@ def lib():
         "sw_last_error": (cp, []),
         "sw_pre_add": (ci, [ci, vp, i64, i64, i64, i64, vp, i64, i64, vp]),
         "sw_post_add": (ci, [vp, i64, i64, i64, i64, vp, i64, i64, vp]),
+        "sw_pre_add2": (ci, [ci, vp, i64, i64, i64, i64, vp, i64, i64, vp]),
+        "sw_post_add2": (ci, [vp, i64, i64, i64, i64, vp, i64, i64, vp]),
         "sw_leaf_gemm": (ci, [i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp]),
         "sw_pad_copy": (ci, [vp, i64, i64, i64, vp, i64, i64, i64, vp]),
         "sw_profile_enable": (ci, [ci]),
@@ -156,6 +158,16 @@ def sw_pre_add(side, parent, parent_ld, parent_stride, live, h, child, child_ld,
 def sw_post_add(Q, q_ld, q_stride, live, h, parent, parent_ld, parent_stride):
     return _check(lib().sw_post_add(_ptr(Q), q_ld, q_stride, live, h, _ptr(parent), parent_ld, parent_stride,
                                     _stream(parent)))
+
+
+def sw_pre_add2(side, parent, parent_ld, parent_stride, live, m, child, child_ld, child_stride):
+    return _check(lib().sw_pre_add2(side, _ptr(parent), parent_ld, parent_stride, live, m, _ptr(child), child_ld,
+                                    child_stride, _stream(child)))
+
+
+def sw_post_add2(Q, q_ld, q_stride, live, m, parent, parent_ld, parent_stride):
+    return _check(lib().sw_post_add2(_ptr(Q), q_ld, q_stride, live, m, _ptr(parent), parent_ld, parent_stride,
+                                     _stream(parent)))
 
 
 def sw_leaf_gemm(m, batch, A, lda, stride_a, B, ldb, stride_b, C, ldc, stride_c):

@@ -11,8 +11,18 @@
 namespace sw {
 namespace {
 
-constexpr int NT = 256;   // threads per block
-constexpr int ROWS = 4;   // rows per thread (independent loads in flight)
+#ifndef SW_ADD_NT_THREADS
+#define SW_ADD_NT_THREADS 256
+#endif
+#ifndef SW_ADD_ROWS
+#define SW_ADD_ROWS 4
+#endif
+#ifndef SW_ADD_POST_ROWS
+#define SW_ADD_POST_ROWS 2
+#endif
+constexpr int NT = SW_ADD_NT_THREADS;   // threads per block
+constexpr int ROWS = SW_ADD_ROWS;       // rows per thread (independent loads in flight)
+constexpr int POST_ROWS = SW_ADD_POST_ROWS;
 
 template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef double type; };
@@ -21,12 +31,20 @@ template <> struct VecT<2> { typedef double __attribute__((ext_vector_type(2))) 
 template <int VEC>
 __device__ __forceinline__ typename VecT<VEC>::type ld(const double* p)
 {
+#ifdef SW_ADD_NT_LOAD
+    return __builtin_nontemporal_load(reinterpret_cast<const typename VecT<VEC>::type*>(p));
+#else
     return *reinterpret_cast<const typename VecT<VEC>::type*>(p);
+#endif
 }
 template <int VEC>
 __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 {
+#ifdef SW_ADD_NT_STORE
+    __builtin_nontemporal_store(v, reinterpret_cast<typename VecT<VEC>::type*>(p));
+#else
     *reinterpret_cast<typename VecT<VEC>::type*>(p) = v;
+#endif
 }
 
 // ---- BFS pre-additions ------------------------------------------------------------------------------------
@@ -99,7 +117,7 @@ post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int 
                 double* __restrict__ parent, int64_t pld, int64_t pstride)
 {
     typedef typename VecT<VEC>::type V;
-    constexpr int R = 2;
+    constexpr int R = POST_ROWS;
     const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
     if (cx >= h) return;
     const int r0 = blockIdx.y * R;
@@ -219,6 +237,119 @@ dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11
     }
 }
 
+// ---- two BFS steps in one pass ------------------------------------------------------------------------------------
+// When two BFS steps follow each other, the operands of the 49 grandchildren are formed straight from the
+// parent: the parent is a 4 x 4 grid of m x m blocks a[R][C]; the first step's T_j (a 2 x 2 block matrix) has
+// blocks T_j[p][q] = f_j(a[p][q], a[p][2+q], a[2+p][q], a[2+p][2+q]) and the second step gives
+// T_{j,i} = f_i(T_j[0][0], T_j[0][1], T_j[1][0], T_j[1][1]), with f the seven combinations of Appendix A in
+// their printed association.  The 28 intermediate blocks live in registers only, so the values are the same
+// bits as two separate steps while the intermediate operands are never written to or read from HBM.
+template <int SIDE, typename V>
+__device__ __forceinline__ void winograd_pre(const V x11, const V x12, const V x21, const V x22, V (&o)[7])
+{
+    if (SIDE == 0) {            // T0..T6 from A's quadrants
+        const V t2 = x21 + x22;
+        const V t3 = t2 - x11;
+        o[0] = x11; o[1] = x12; o[2] = t2; o[3] = t3; o[4] = x11 - x21; o[5] = x12 - t3; o[6] = x22;
+    } else {                    // S0..S6 from B's quadrants
+        const V s2 = x12 - x11;
+        const V s3 = x22 - s2;
+        o[0] = x11; o[1] = x21; o[2] = s2; o[3] = s3; o[4] = x22 - x12; o[5] = x22; o[6] = s3 - x21;
+    }
+}
+
+template <int SIDE, int VEC>
+__global__ void __launch_bounds__(NT)
+pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int m,
+                double* __restrict__ child, int64_t cld, int64_t cstride)
+{
+    typedef typename VecT<VEC>::type V;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    const int row = blockIdx.y;
+    if (cx >= m) return;
+    const double* P = parent + (int64_t)blockIdx.z * pstride + (int64_t)row * pld + cx;
+    double* O = child + (int64_t)blockIdx.z * 49 * cstride + (int64_t)row * cld + cx;
+
+    V a[4][4];
+#pragma unroll
+    for (int R = 0; R < 4; ++R)
+#pragma unroll
+        for (int C = 0; C < 4; ++C) a[R][C] = ld<VEC>(P + (int64_t)R * m * pld + C * m);
+
+    V t[4][7];   // t[2p+q][j] = T_j[p][q]
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) winograd_pre<SIDE, V>(a[p][q], a[p][2 + q], a[2 + p][q], a[2 + p][2 + q], t[2 * p + q]);
+#pragma unroll
+    for (int j = 0; j < 7; ++j) {
+        V o[7];
+        winograd_pre<SIDE, V>(t[0][j], t[1][j], t[2][j], t[3][j], o);
+#pragma unroll
+        for (int i = 0; i < 7; ++i) st<VEC>(O + (int64_t)(j * 7 + i) * cstride, o[i]);
+    }
+}
+
+// The reverse for the products: q[j][i] are the 49 grandchild products; Q_j[p][q] is the post-addition of
+// q[j][0..6] (Appendix A, fourth column) and the parent's block c[2X+p][2Y+q] the same post-addition over j.
+template <int VEC>
+__global__ void __launch_bounds__(NT)
+post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int m,
+                 double* __restrict__ parent, int64_t pld, int64_t pstride)
+{
+    typedef typename VecT<VEC>::type V;
+    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
+    const int row = blockIdx.y;
+    if (cx >= m) return;
+    const double* q = Q + (int64_t)blockIdx.z * 49 * qstride + (int64_t)row * qld + cx;
+    double* P = parent + (int64_t)blockIdx.z * pstride + (int64_t)row * pld + cx;
+
+    // Q_j as four blocks [11, 12, 21, 22] from the seven products of child j
+    auto child = [&](int j, V (&out)[4]) __attribute__((always_inline)) {
+        V v[7];
+#pragma unroll
+        for (int i = 0; i < 7; ++i) v[i] = ld<VEC>(q + (int64_t)(j * 7 + i) * qstride);
+        const V u1 = v[0] + v[3];
+        const V u2 = u1 + v[4];
+        const V u3 = u1 + v[2];
+        out[0] = v[0] + v[1];
+        out[1] = u3 + v[5];
+        out[2] = u2 - v[6];
+        out[3] = u2 + v[2];
+    };
+    // store the four blocks of the parent's quadrant (X, Y)
+    auto put = [&](int X, int Y, const V (&c)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pq = 0; pq < 4; ++pq)
+            st<VEC>(P + (int64_t)(2 * X + (pq >> 1)) * m * pld + (2 * Y + (pq & 1)) * m, c[pq]);
+    };
+
+    V q0[4], q3[4], u1[4], u2[4], u3[4], t[4], c[4];
+    child(0, q0);
+    child(3, q3);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) u1[k] = q0[k] + q3[k];          // U1 = Q0 + Q3
+    child(1, t);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = q0[k] + t[k];            // C11 = Q0 + Q1
+    put(0, 0, c);
+    child(4, t);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) u2[k] = u1[k] + t[k];           // U2 = U1 + Q4
+    child(2, t);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { u3[k] = u1[k] + t[k]; c[k] = u2[k] + t[k]; }   // U3 = U1 + Q2, C22 = U2 + Q2
+    put(1, 1, c);
+    child(5, t);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = u3[k] + t[k];            // C12 = U3 + Q5
+    put(0, 1, c);
+    child(6, t);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = u2[k] - t[k];            // C21 = U2 - Q6
+    put(1, 0, c);
+}
+
 // ---- zero-padded copy ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT)
 pad_copy_kernel(const double* __restrict__ src, int64_t sld, int rows, int cols, double* __restrict__ dst,
@@ -267,12 +398,40 @@ hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream
 {
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(q);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, 2, live);
+    const dim3 g = grid_for(h, v2 ? 2 : 1, POST_ROWS, live);
     if (v2)
         hipLaunchKernelGGL((post_add_kernel<2>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
                            parent.ld, parent.stride);
     else
         hipLaunchKernelGGL((post_add_kernel<1>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+                           parent.ld, parent.stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat child, hipStream_t s)
+{
+    if (live == 0 || m == 0) return hipSuccess;
+    const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(child);
+    const dim3 g = grid_for(m, v2 ? 2 : 1, 1, live);
+#define SW_LAUNCH(SIDE, VEC)                                                                               \
+    hipLaunchKernelGGL((pre_add2_kernel<SIDE, VEC>), g, dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
+                       (int)m, child.p, child.ld, child.stride)
+    if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
+    else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
+#undef SW_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStream_t s)
+{
+    if (live == 0 || m == 0) return hipSuccess;
+    const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(q);
+    const dim3 g = grid_for(m, v2 ? 2 : 1, 1, live);
+    if (v2)
+        hipLaunchKernelGGL((post_add2_kernel<2>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
+                           parent.ld, parent.stride);
+    else
+        hipLaunchKernelGGL((post_add2_kernel<1>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
                            parent.ld, parent.stride);
     return hipGetLastError();
 }

@@ -190,7 +190,23 @@ struct Exec {
         const int64_t h = n / 2;
         const int64_t ld = ws_ld(h), e = ws_mat_elems(h);
         const int64_t mark = used;
-        if (sched[level] == 'B') {
+        if (fuse_two_bfs(sched + level)) {
+            // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
+            // their products go straight back; the level in between exists in registers only
+            const int64_t m = h / 2;
+            const int64_t ld4 = ws_ld(m), e4 = ws_mat_elems(m);
+            Mat T{take(49 * live * e4), ld4, e4}, S{take(49 * live * e4), ld4, e4}, Q{take(49 * live * e4), ld4, e4};
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49));
+            note(launch_pre_add2(0, A, live, m, T, stream));
+            prof_end(prof, stream);
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49));
+            note(launch_pre_add2(1, B, live, m, S, stream));
+            prof_end(prof, stream);
+            mul(T, S, Q, m, level + 2, 49 * live);
+            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, m, 49, 16));
+            note(launch_post_add2(Q, live, m, C, stream));
+            prof_end(prof, stream);
+        } else if (sched[level] == 'B') {
             // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
             Mat T{take(7 * live * e), ld, e}, S{take(7 * live * e), ld, e}, Q{take(7 * live * e), ld, e};
             prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
@@ -428,6 +444,30 @@ int sw_post_add(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, i
     hipError_t e = launch_post_add(Mat{const_cast<double*>(Q), q_ld, q_stride}, live, h,
                                    Mat{parent, parent_ld, parent_stride}, (hipStream_t)hip_stream);
     return e == hipSuccess ? SW_OK : hip_fail(e, "sw_post_add");
+}
+
+int sw_pre_add2(int side, const double* parent, int64_t parent_ld, int64_t parent_stride, int64_t live,
+                int64_t m, double* child, int64_t child_ld, int64_t child_stride, void* hip_stream)
+{
+    if ((side != 0 && side != 1) || bad_dims(live, m) || m > 65535 || !parent || !child || parent_ld < 4 * m || child_ld < m) {
+        set_error("sw_pre_add2: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_pre_add2(side, Mat{const_cast<double*>(parent), parent_ld, parent_stride}, live, m,
+                                   Mat{child, child_ld, child_stride}, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_pre_add2");
+}
+
+int sw_post_add2(const double* Q, int64_t q_ld, int64_t q_stride, int64_t live, int64_t m, double* parent,
+                 int64_t parent_ld, int64_t parent_stride, void* hip_stream)
+{
+    if (bad_dims(live, m) || m > 65535 || !Q || !parent || parent_ld < 4 * m || q_ld < m) {
+        set_error("sw_post_add2: bad argument");
+        return SW_EINVAL;
+    }
+    hipError_t e = launch_post_add2(Mat{const_cast<double*>(Q), q_ld, q_stride}, live, m,
+                                    Mat{parent, parent_ld, parent_stride}, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_post_add2");
 }
 
 int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t stride_a, const double* B,

@@ -25,15 +25,29 @@ inline int64_t ws_ld(int64_t h)
 // Elements reserved for one h x h workspace matrix (a multiple of 32 doubles = 256 bytes).
 inline int64_t ws_mat_elems(int64_t h) { return (ws_ld(h) * h + 31) / 32 * 32; }
 
+// A run of consecutive BFS steps is executed in fused pairs, deepest pairs first: with an even number of B
+// ahead the next two steps share one pass and the operands of the level between them are never stored.
+inline bool fuse_two_bfs(const char* sched)
+{
+    int run = 0;
+    while (sched[run] == 'B') ++run;
+    return run >= 2 && run % 2 == 0;
+}
+
 // Bytes of workspace the executor takes for an np x np problem (np a multiple of 2^levels) whose remaining
 // step order is `sched`, entered with `live` parents.  BFS step: T, S, Q for all seven children of every
-// parent (Section 3.3.1); DFS step: two temporaries per parent, because products are written straight into
-// the parent's C quadrants (the footnote of Section 3.3.1 allows a few temporaries).
+// parent (Section 3.3.1), or for all 49 grandchildren when two BFS steps are fused; DFS step: two
+// temporaries per parent, because products are written straight into the parent's C quadrants (the footnote
+// of Section 3.3.1 allows a few temporaries).
 inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live)
 {
     if (*sched == '\0') return 0;
     const int64_t h = n / 2;
     const int64_t e = ws_mat_elems(h) * (int64_t)sizeof(double);
+    if (fuse_two_bfs(sched)) {
+        const int64_t e4 = ws_mat_elems(h / 2) * (int64_t)sizeof(double);
+        return 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live);
+    }
     if (*sched == 'B') return 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live);
     return 2 * live * e + ws_need_bytes(h, sched + 1, live);
 }
@@ -72,6 +86,9 @@ inline Mat quad(const Mat& m, int64_t h, int i, int j) { return Mat{m.p + i * h 
 hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, hipStream_t s);
 // BFS post-additions, Appendix A column 4.
 hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s);
+// Two consecutive BFS steps in one pass: parent of size 4m -> 49 grandchildren of size m, and back.
+hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat child, hipStream_t s);
+hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStream_t s);
 // Z = X + sign * Y on h x h matrices, `live` of them; Z may be X or Y itself.
 hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s);
 // Two independent such operations in one launch (the A-side and B-side pre-addition of a DFS step).

@@ -121,6 +121,33 @@ def test_pre_and_post_add_bitwise(h, live):
     assert np.array_equal(q(got, 1, 1), u2 + hQ[:, 2])
 
 
+@pytest.mark.parametrize("m,live", [(5, 1), (64, 2), (147, 3), (200, 1)])
+def test_fused_two_step_additions_equal_two_single_steps(m, live):
+    # sw_pre_add2 / sw_post_add2 must give the very bits of two sw_pre_add / sw_post_add passes
+    n, h = 4 * m, 2 * m
+    ld = lambda x: (x + 15) // 16 * 16
+    P = torch.from_numpy(np.stack([inputs.matrix(n, 70 + p, 0, "uniform") for p in range(live)])).to(DEV)
+    for side in (0, 1):
+        mid = torch.empty((live * 7, h, ld(h)), dtype=torch.float64, device=DEV)
+        sw.sw_pre_add(side, P, n, n * n, live, h, mid, ld(h), h * ld(h))
+        two = torch.full((live * 49, m, ld(m)), float("nan"), dtype=torch.float64, device=DEV)
+        sw.sw_pre_add(side, mid, ld(h), h * ld(h), live * 7, m, two, ld(m), m * ld(m))
+        one = torch.full((live * 49, m, ld(m)), float("nan"), dtype=torch.float64, device=DEV)
+        sw.sw_pre_add2(side, P, n, n * n, live, m, one, ld(m), m * ld(m))
+        torch.cuda.synchronize()
+        assert torch.equal(one[:, :, :m], two[:, :, :m]), side
+        assert torch.isnan(one[:, :, m:]).all()
+    Q = torch.from_numpy(np.stack([inputs.matrix(m, 300 + i, 1, "uniform") for i in range(live * 49)])).to(DEV)
+    mid = torch.empty((live * 7, h, h), dtype=torch.float64, device=DEV)
+    sw.sw_post_add(Q, m, m * m, live * 7, m, mid, h, h * h)
+    two = torch.empty((live, n, n), dtype=torch.float64, device=DEV)
+    sw.sw_post_add(mid, h, h * h, live, h, two, n, n * n)
+    one = torch.full((live, n, n), float("nan"), dtype=torch.float64, device=DEV)
+    sw.sw_post_add2(Q, m, m * m, live, m, one, n, n * n)
+    torch.cuda.synchronize()
+    assert torch.equal(one, two)
+
+
 def test_pad_copy_and_crop():
     src = torch.from_numpy(inputs.matrix(37, 1, 0, "uniform")).to(DEV)
     dst = torch.full((40, 48), float("nan"), dtype=torch.float64, device=DEV)
@@ -145,7 +172,8 @@ CASES = [
     (1001, 3, ["DBB", "BDD"], "uniform"),                     # padded to 1008, leaf 126
     (777, 2, ["BB", "DB"], "uniform"),                        # padded to 780, leaf 195
     (2940, 2, ["DB", "BB"], "uniform"),                       # leaf 735 as in configuration 4
-    (96, 5, ["BDBDB", "DDDDD", "BBBBB"], "uniform"),          # leaf 3
+    (96, 5, ["BDBDB", "DDDDD", "BBBBB", "DBBBB", "BBDBB"], "uniform"),   # leaf 3; odd and even runs of BFS steps
+    (1200, 4, ["BBBB", "DBBB", "DDBB", "BBDB"], "uniform"),   # leaf 75; fused pairs of BFS steps
     (300, 0, [""], "uniform"),                                # no Strassen step at all
     (1, 0, [""], "uniform"),
 ]

@@ -61,6 +61,10 @@ def test_plan_memory_structure():
     assert sw.sw_plan_memory(1024, 2, "DB") == (2 * elems(512) + 21 * elems(256)) * 8
     assert sw.sw_plan_memory(1024, 2, "BD") == (21 * elems(512) + 2 * 7 * elems(256)) * 8
     assert sw.sw_plan_memory(1024, 2, None) == sw.sw_plan_memory(1024, 2, "DD")
+    # two BFS steps in a row are fused: operands of the 49 grandchildren only, nothing for the level between
+    assert sw.sw_plan_memory(1024, 2, "BB") == 3 * 49 * elems(256) * 8
+    assert sw.sw_plan_memory(1024, 3, "BBB") == (21 * elems(512) + 3 * 49 * 7 * elems(128)) * 8   # odd run: top step alone
+    assert sw.sw_plan_memory(1024, 3, "DBB") == (2 * elems(512) + 3 * 49 * elems(128)) * 8
     assert sw.sw_plan_memory(1024, 0, "") == 0
     # padding: 1001 -> 1008 with three padded copies
     assert sw.sw_plan_memory(1001, 3, "DDD") == sw.sw_plan_memory(1008, 3, "DDD") + 3 * elems(1008) * 8
