@@ -53,6 +53,20 @@ def cpu_baseline(n, levels):
                       f"{levels}-level product"}
 
 
+def measured_traffic(m, batch):
+    """HBM bytes per leaf-GEMM launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE
+    runs, each scaled by a copy kernel of known size); None when no summary covers this launch shape."""
+    path = os.path.join(ROOT, "profiles", f"leaf_gemm_m{m}_b{batch}_pmc.txt")
+    key = f"leaf_gemm_m{m}_b{batch}_traffic_bytes_per_launch="
+    try:
+        for line in open(path):
+            if line.startswith(key):
+                return float(line[len(key):])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,10 +116,12 @@ def main():
     eff_gflops = 2.0 * n ** 3 / (dt / args.steps) / 1e9
 
     leaf = prof["leaf_gemm"]
+    leaf_batch = 7 ** schedule.count("B")            # leaves per launch: the batch grows sevenfold at every BFS step
     leaf_tflops = leaf["work"] / (leaf["ms"] * 1e-3) / 1e12 if leaf["ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": "leaf_gemm_kernel (batched fp64 MFMA)",
                 "achieved": round(leaf_tflops, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(leaf_tflops / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(leaf_tflops / FP64_MFMA_PEAK_TFLOPS, 4),
+                "traffic": measured_traffic(n >> levels, leaf_batch),
                 "launches": leaf["launches"], "avg_launch_ms": round(leaf["ms"] / max(1, leaf["launches"]), 4),
                 "flops_per_launch": leaf["work"] / max(1, leaf["launches"])}
     adds = {}
