@@ -1,7 +1,8 @@
 // Streaming kernels of the Strassen-Winograd step: the pre-additions that form the T and S operands, the
 // post-additions that turn the seven products into the four quadrants of C (Appendix A), the element-wise
 // pieces of a DFS step, and the zero-padded copy.  All are HBM-bound: every kernel reads each input element
-// once and writes each output element once, with 16-byte accesses when alignment allows (8-byte otherwise).
+// once and writes each output element once, with 16-byte accesses when alignment allows (8-byte otherwise) and
+// non-temporal hints (every operand is far larger than the caches and is next touched by another kernel).
 //
 // Thread layout, common to all kernels: threadIdx.x walks columns in units of VEC doubles, blockIdx.y walks
 // groups of ROWS rows, blockIdx.z is the matrix of the batch.  Adjacent lanes touch adjacent addresses, so a
@@ -15,7 +16,7 @@ namespace {
 #define SW_ADD_NT_THREADS 256
 #endif
 #ifndef SW_ADD_ROWS
-#define SW_ADD_ROWS 4
+#define SW_ADD_ROWS 2
 #endif
 #ifndef SW_ADD_POST_ROWS
 #define SW_ADD_POST_ROWS 2
@@ -31,7 +32,7 @@ template <> struct VecT<2> { typedef double __attribute__((ext_vector_type(2))) 
 template <int VEC>
 __device__ __forceinline__ typename VecT<VEC>::type ld(const double* p)
 {
-#ifdef SW_ADD_NT_LOAD
+#ifndef SW_ADD_TEMPORAL   /* streaming data: nothing here is read again before it has left every cache */
     return __builtin_nontemporal_load(reinterpret_cast<const typename VecT<VEC>::type*>(p));
 #else
     return *reinterpret_cast<const typename VecT<VEC>::type*>(p);
@@ -40,7 +41,7 @@ __device__ __forceinline__ typename VecT<VEC>::type ld(const double* p)
 template <int VEC>
 __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 {
-#ifdef SW_ADD_NT_STORE
+#ifndef SW_ADD_TEMPORAL
     __builtin_nontemporal_store(v, reinterpret_cast<typename VecT<VEC>::type*>(p));
 #else
     *reinterpret_cast<typename VecT<VEC>::type*>(p) = v;
