@@ -36,7 +36,7 @@ def cpu_baseline(n, levels):
     from paper_1202_3173_amd import binding, inputs
     m = n >> levels
     reps = 1
-    while reps * 2.0 * m ** 3 < 2e10 and reps < 4096:      # at least ~20 GFLOP of work for small leaves
+    while reps * 2.0 * m ** 3 < 1e11 and reps < 65536:     # about 100 GFLOP of CPU work: 10-20 s on one core
         reps *= 2
     A = inputs.matrix(m, 99, 0, "uniform")
     B = inputs.matrix(m, 99, 1, "uniform")
