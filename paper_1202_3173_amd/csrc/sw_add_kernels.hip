@@ -24,6 +24,7 @@ namespace {
 constexpr int NT = SW_ADD_NT_THREADS;   // threads per block
 constexpr int ROWS = SW_ADD_ROWS;       // rows per thread (independent loads in flight)
 constexpr int POST_ROWS = SW_ADD_POST_ROWS;
+constexpr int PAD_ROWS = 8;              // rows per thread of the pad / crop copy
 
 template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef double type; };
@@ -358,9 +359,9 @@ pad_copy_kernel(const double* __restrict__ src, int64_t sld, int rows, int cols,
 {
     const int c = blockIdx.x * NT + threadIdx.x;
     if (c >= pcols) return;
-    const int r0 = blockIdx.y * ROWS;
+    const int r0 = blockIdx.y * PAD_ROWS;
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
+    for (int r = 0; r < PAD_ROWS; ++r) {
         const int row = r0 + r;
         if (row < prows) {
             const double v = (row < rows && c < cols) ? src[(int64_t)row * sld + c] : 0.0;
@@ -485,7 +486,7 @@ hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int6
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s)
 {
     if (prows == 0 || pcols == 0) return hipSuccess;
-    const dim3 g((unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + ROWS - 1) / ROWS), 1);
+    const dim3 g((unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + PAD_ROWS - 1) / PAD_ROWS), 1);
     hipLaunchKernelGGL(pad_copy_kernel, g, dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
                        (int)prows, (int)pcols);
     return hipGetLastError();

@@ -21,7 +21,8 @@
 //     share A row panels and B column panels through that L2;
 //   * edges: rows and columns beyond m are clamped to the last valid one on load (their products land in
 //     accumulators that are never stored); the K tail is zero-filled; stores are bounds-checked.  16-byte
-//     global loads when pointers, leading dimensions and m allow it, 8-byte loads otherwise.
+//     global loads when pointers and leading dimensions allow it (an odd m too, if rows are padded),
+//     8-byte loads otherwise.
 #include <type_traits>
 
 #include "sw_internal.h"
@@ -106,12 +107,14 @@ leaf_gemm_kernel(const GemmArgs g)
     // BYTE offsets from the uniform panel bases (rows / columns clamped into the matrix).  They stay below
     // 128 * ld * 8 < 2^32, so every load is "uniform 64-bit base in SGPRs + 32-bit per-lane offset" and
     // the K loop advances the bases with scalar adds only: no vector ALU work competes with the MFMAs.
+    // last column (pair) a lane may load: with VEC == 2 and odd N the pair N - 1, N reaches into the padding
+    const int b_cmax = (VEC == 2 ? ((g.N - 1) & ~1) : g.N - 1) - n0;
     unsigned offA[NL], offB[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
         const int row = min(a_r0 + i * A_RSTEP, g.M - 1 - m0);
         offA[i] = ((unsigned)((int64_t)row * g.lda) + (unsigned)a_k) * 8u;
-        offB[i] = ((unsigned)((int64_t)(b_k0 + i * B_KSTEP) * g.ldb) + (unsigned)min(b_c, g.N - VEC - n0)) * 8u;
+        offB[i] = ((unsigned)((int64_t)(b_k0 + i * B_KSTEP) * g.ldb) + (unsigned)min(b_c, b_cmax)) * 8u;
     }
 
     V ra[NL], rb[NL];
@@ -134,18 +137,27 @@ leaf_gemm_kernel(const GemmArgs g)
     };
     // the last slab when it reaches beyond K: k is clamped for the address and the value zero-filled
     auto gload_tail = [&](int k0) __attribute__((always_inline)) {
-        const bool a_ok = k0 + a_k < g.K;                            // VEC == 2: K even, the pair is in or out
-        const int a_back = a_ok ? 0 : ((k0 + a_k) - (g.K - VEC)) * 8;  // bytes to step back inside the row
+        // A: the lane's k (VEC == 2: the pair k, k + 1; with odd K the pair K - 1, K reaches into the row's
+        // padding, which the caller guarantees to exist, and that element is zeroed)
+        const int k = k0 + a_k;
+        const int kc = min(k, VEC == 2 ? ((g.K - 1) & ~1) : g.K - 1);   // last load position inside the row
+        const int a_back = (k - kc) * 8;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const V v = *reinterpret_cast<const V*>(reinterpret_cast<const char*>(A + k0) + ((int64_t)offA[i] - a_back));
-            ra[i] = a_ok ? v : V(0.0);
+            V v = *reinterpret_cast<const V*>(reinterpret_cast<const char*>(A + k0) + ((int64_t)offA[i] - a_back));
+            if constexpr (VEC == 2) {
+                if (k >= g.K) v[0] = 0.0;
+                if (k + 1 >= g.K) v[1] = 0.0;
+            } else {
+                if (k >= g.K) v = 0.0;
+            }
+            ra[i] = v;
         }
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int k = k0 + b_k0 + i * B_KSTEP;
-            const bool ok = k < g.K;
-            const int64_t back = ok ? 0 : (int64_t)(k - (g.K - 1)) * g.ldb * 8;
+            const int kb = k0 + b_k0 + i * B_KSTEP;
+            const bool ok = kb < g.K;
+            const int64_t back = ok ? 0 : (int64_t)(kb - (g.K - 1)) * g.ldb * 8;
             const V v = *reinterpret_cast<const V*>(reinterpret_cast<const char*>(B + (int64_t)k0 * g.ldb) + ((int64_t)offB[i] - back));
             rb[i] = ok ? v : V(0.0);
         }
@@ -305,8 +317,10 @@ hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipSt
     g.tiles_n = (int)((m + BN - 1) / BN);
     const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * batch;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const bool v2 = (m % 2 == 0) && aligned16(a.p) && aligned16(b.p) && a.ld % 2 == 0 && b.ld % 2 == 0 &&
-                    a.stride % 2 == 0 && b.stride % 2 == 0;
+    // 16-byte loads need aligned pairs; an odd m is fine when every row has padding behind it (the library's
+    // own workspace matrices do), because the pair that straddles the edge then still reads inside the row
+    const bool v2 = aligned16(a.p) && aligned16(b.p) && a.ld % 2 == 0 && b.ld % 2 == 0 && a.stride % 2 == 0 &&
+                    b.stride % 2 == 0 && (m % 2 == 0 || (a.ld > m && b.ld > m));
     if (v2) hipLaunchKernelGGL((leaf_gemm_kernel<2>), dim3((unsigned)blocks), dim3(NT), 0, s, g);
     else    hipLaunchKernelGGL((leaf_gemm_kernel<1>), dim3((unsigned)blocks), dim3(NT), 0, s, g);
     return hipGetLastError();

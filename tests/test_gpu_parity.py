@@ -46,10 +46,12 @@ def test_device_generator_matches_host(dist):
 # ---- leaf products ------------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("m,batch,ldpad", [(1, 1, 0), (16, 3, 0), (100, 2, 0), (128, 1, 0), (129, 2, 1),
-                                           (255, 1, 1), (256, 2, 0), (300, 3, 4), (735, 2, 1), (514, 1, 2)])
+                                           (255, 1, 1), (256, 2, 0), (300, 3, 4), (735, 2, 1), (514, 1, 2),
+                                           (735, 2, 3), (129, 3, 3), (5, 2, 3), (143, 1, 17)])
 def test_leaf_gemm_against_classical_oracle(oracle, m, batch, ldpad):
     ld = m + ldpad
-    stride = ld * m + 7 * (ldpad % 2)      # odd strides force the 8-byte load path
+    stride = ld * m + (7 if ldpad == 1 else 0)   # ldpad 1: odd stride, the 8-byte load path; odd m with an
+    #                                              even padded pitch and stride: 16-byte loads that straddle the edge
     hA = [inputs.matrix(m, 3 + b, 0, "uniform") for b in range(batch)]
     hB = [inputs.matrix(m, 3 + b, 1, "uniform") for b in range(batch)]
     A = torch.zeros(batch * stride, dtype=torch.float64, device=DEV)
