@@ -84,6 +84,16 @@ double sw_flop_count(int64_t n, int levels);
 
 int sw_set_workspace(void* dev_ptr, int64_t bytes); /* caller-owned; NULL/0 clears it                    */
 int sw_set_stream(void* hip_stream);                /* hipStream_t; NULL = the null stream               */
+
+/* What sw_gemm, sw_plan_memory and sw_plan_schedule do when 2^levels does not divide n (Section 3.1:
+ * "padding or dynamic peeling").  SW_ODD_PAD (default): zero-padded workspace copies of A, B, C of the next
+ * multiple.  SW_ODD_PEEL: the recursion runs in place on the leading blocks of the previous multiple n0 and
+ * the n - n0 < 2^levels peeled rows and columns are finished by thin classical products (C11 += A12*B21,
+ * C12 = [A11 A12]*[B12;B22], [C21 C22] = [A21 A22]*B); no copies, so it also works when three more matrices
+ * do not fit. */
+#define SW_ODD_PAD 0
+#define SW_ODD_PEEL 1
+int sw_set_odd_mode(int mode);
 const char* sw_last_error(void);                    /* HOST string, valid until the thread's next call  */
 
 /* ---- the steps of the path, one call each (used by sw_gemm; exported so each can be tested and timed) ---- */
@@ -116,6 +126,11 @@ int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t
                  const double* B, int64_t ldb, int64_t stride_b, double* C, int64_t ldc, int64_t stride_c,
                  void* hip_stream);
 
+/* The leaf kernel on general shapes: C (M x N) = A (M x K) * B (K x N), or C += A * B if accumulate != 0.
+ * Used by peeling; any M, N, K >= 0 (K = 0 with accumulate == 0 zeroes C). */
+int sw_gemm_classical(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, const double* B, int64_t ldb,
+                      double* C, int64_t ldc, int accumulate, void* hip_stream);
+
 /* Zero-padded copy (rows x cols of src into the top-left of a prows x pcols dst, rest zero) and its
  * inverse crop are the same call: the region copied is min(rows, prows) x min(cols, pcols). */
 int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
@@ -129,7 +144,8 @@ int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
 #define SW_CLASS_LEAF 2     /* batched leaf GEMM                        */
 #define SW_CLASS_DFS_ADD 3  /* element-wise kernels of DFS steps        */
 #define SW_CLASS_PAD 4      /* pad / crop copies                        */
-#define SW_NUM_CLASSES 5
+#define SW_CLASS_PEEL 5     /* thin classical products of peeling (work = flops) */
+#define SW_NUM_CLASSES 6
 
 /* on != 0: bracket every kernel launch of sw_gemm with HIP events on the launch stream (no host sync).
  * sw_profile_read synchronises those events, adds up per class the elapsed milliseconds, the launches and

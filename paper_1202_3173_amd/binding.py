@@ -9,10 +9,11 @@ LIB_PATH = os.environ.get("SW_GEMM_LIB") or os.path.join(_HERE, "libsw_gemm.so")
 
 SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
 SW_MAX_LEVELS = 16
-CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad")
+CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel")
+SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
-           "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_last_error", "sw_pre_add", "sw_post_add",
+           "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
 
 
@@ -44,6 +45,8 @@ def lib():
         "sw_flop_count": (dbl, [i64, ci]),
         "sw_set_workspace": (ci, [vp, i64]),
         "sw_set_stream": (ci, [vp]),
+        "sw_set_odd_mode": (ci, [ci]),
+        "sw_gemm_classical": (ci, [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]),
         "sw_last_error": (cp, []),
         "sw_pre_add": (ci, [ci, vp, i64, i64, i64, i64, vp, i64, i64, vp]),
         "sw_post_add": (ci, [vp, i64, i64, i64, i64, vp, i64, i64, vp]),
@@ -129,6 +132,15 @@ def sw_set_workspace(ws):
 
 def sw_set_stream(stream_handle):
     return _check(lib().sw_set_stream(ctypes.c_void_p(stream_handle)))
+
+
+def sw_set_odd_mode(mode):
+    return _check(lib().sw_set_odd_mode(mode))
+
+
+def sw_gemm_classical(M, N, K, A, lda, B, ldb, C, ldc, accumulate=False):
+    return _check(lib().sw_gemm_classical(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, 1 if accumulate else 0,
+                                          _stream(C)))
 
 
 def sw_gemm(n, A, B, C, levels, schedule=None):

@@ -35,6 +35,7 @@ int hip_fail(hipError_t e, const char* what)
 static void* g_ws = nullptr;
 static int64_t g_ws_bytes = 0;
 static hipStream_t g_stream = nullptr;
+static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divide n
 
 // ---- profiling ------------------------------------------------------------------------------------------------
 
@@ -97,10 +98,12 @@ static int check_shape(int64_t n, int levels)
     return SW_OK;
 }
 
-// Total workspace bytes for (n, schedule), including padded copies of A, B, C when needed.
+// Total workspace bytes for (n, schedule): with padding the recursion runs on the next multiple of 2^levels
+// and needs padded copies of A, B, C; with peeling it runs in place on the previous multiple.
 static int64_t total_need(int64_t n, int levels, const char* sched)
 {
     if (n == 0) return 0;
+    if (g_odd_mode == SW_ODD_PEEL) return ws_need_bytes(n - n % ((int64_t)1 << levels), sched, 1);
     const int64_t np = padded_n(n, levels);
     int64_t bytes = ws_need_bytes(np, sched, 1);
     if (np != n) bytes += 3 * ws_mat_elems(np) * (int64_t)sizeof(double);
@@ -188,14 +191,14 @@ struct Exec {
             return;
         }
         const int64_t h = n / 2;
-        const int64_t ld = ws_ld(h), e = ws_mat_elems(h);
+        const int64_t e = ws_mat_elems(h);
         const int64_t mark = used;
         if (fuse_two_bfs(sched + level)) {
             // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
             // their products go straight back; the level in between exists in registers only
             const int64_t m = h / 2;
-            const int64_t ld4 = ws_ld(m), e4 = ws_mat_elems(m);
-            Mat T{take(49 * live * e4), ld4, e4}, S{take(49 * live * e4), ld4, e4}, Q{take(49 * live * e4), ld4, e4};
+            const int64_t e4 = ws_mat_elems(m);
+            Mat T = ws_mat(take(49 * live * e4), m), S = ws_mat(take(49 * live * e4), m), Q = ws_mat(take(49 * live * e4), m);
             prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49));
             note(launch_pre_add2(0, A, live, m, T, stream));
             prof_end(prof, stream);
@@ -208,7 +211,7 @@ struct Exec {
             prof_end(prof, stream);
         } else if (sched[level] == 'B') {
             // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
-            Mat T{take(7 * live * e), ld, e}, S{take(7 * live * e), ld, e}, Q{take(7 * live * e), ld, e};
+            Mat T = ws_mat(take(7 * live * e), h), S = ws_mat(take(7 * live * e), h), Q = ws_mat(take(7 * live * e), h);
             prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
             note(launch_pre_add(0, A, live, h, T, stream));
             prof_end(prof, stream);
@@ -223,7 +226,7 @@ struct Exec {
             // DFS step: the seven products one after the other (Section 3.4), written straight into the
             // quadrants of C, with two temporaries X, Y per parent.  The additions are those of Appendix A
             // in the printed association, so the result is bit-identical to the BFS form.
-            Mat X{take(live * e), ld, e}, Y{take(live * e), ld, e};
+            Mat X = ws_mat(take(live * e), h), Y = ws_mat(take(live * e), h);
             const Mat A11 = quad(A, h, 0, 0), A12 = quad(A, h, 0, 1), A21 = quad(A, h, 1, 0), A22 = quad(A, h, 1, 1);
             const Mat B11 = quad(B, h, 0, 0), B12 = quad(B, h, 0, 1), B21 = quad(B, h, 1, 0), B22 = quad(B, h, 1, 1);
             const Mat C11 = quad(C, h, 0, 0), C12 = quad(C, h, 0, 1), C21 = quad(C, h, 1, 0), C22 = quad(C, h, 1, 1);
@@ -301,24 +304,41 @@ static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, i
     ex.levels = levels;
     ex.prof = profiler();
 
-    const int64_t np = padded_n(n, levels);
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
-    if (np != n) {
-        // zero-pad into workspace copies of the next multiple of 2^levels (Section 3.1)
-        const int64_t ld = ws_ld(np), e = ws_mat_elems(np);
-        a = Mat{ex.take(e), ld, 0};
-        b = Mat{ex.take(e), ld, 0};
-        c = Mat{ex.take(e), ld, 0};
-        prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np));
-        ex.note(launch_pad_copy(A, lda, n, n, a.p, ld, np, np, stream));
-        ex.note(launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, stream));
+    const int64_t r = n % ((int64_t)1 << levels);
+    if (r != 0 && g_odd_mode == SW_ODD_PEEL) {
+        // Peeling (Section 3.1 names it beside padding): the leading n0 x n0 blocks, n0 the previous multiple
+        // of 2^levels, go through the recursion in place; the r < 2^levels peeled rows and columns are
+        // finished by three thin classical products on the same MFMA kernel.
+        const int64_t n0 = n - r;
+        ex.mul(a, b, c, n0, 0, 1);                                   // C11  = A11 * B11
+        prof_begin(ex.prof, stream, SW_CLASS_PEEL, 2.0 * r * ((double)n0 * n0 + 2.0 * (double)n * n0 + (double)n * r));
+        const Mat a12{a.p + n0, lda, 0}, b21{b.p + n0 * ldb, ldb, 0};
+        ex.note(launch_gemm(n0, n0, r, 1, a12, b21, c, true, stream));                        // C11 += A12 * B21
+        const Mat bright{b.p + n0, ldb, 0}, c12{c.p + n0, ldc, 0};
+        ex.note(launch_gemm(n0, r, n, 1, a, bright, c12, false, stream));                     // C12  = [A11 A12] * [B12; B22]
+        const Mat abot{a.p + n0 * lda, lda, 0}, cbot{c.p + n0 * ldc, ldc, 0};
+        ex.note(launch_gemm(r, n, n, 1, abot, b, cbot, false, stream));                       // [C21 C22] = [A21 A22] * B
         prof_end(ex.prof, stream);
-    }
-    ex.mul(a, b, c, np, 0, 1);
-    if (np != n) {
-        prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * 2.0 * n * n);
-        ex.note(launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, stream));
-        prof_end(ex.prof, stream);
+    } else {
+        const int64_t np = padded_n(n, levels);
+        if (np != n) {
+            // zero-pad into workspace copies of the next multiple of 2^levels (Section 3.1)
+            const int64_t ld = ws_ld(np), e = ws_mat_elems(np);
+            a = Mat{ex.take(e), ld, 0, ld > np};
+            b = Mat{ex.take(e), ld, 0, ld > np};
+            c = Mat{ex.take(e), ld, 0, ld > np};
+            prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np));
+            ex.note(launch_pad_copy(A, lda, n, n, a.p, ld, np, np, stream));
+            ex.note(launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, stream));
+            prof_end(ex.prof, stream);
+        }
+        ex.mul(a, b, c, np, 0, 1);
+        if (np != n) {
+            prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * 2.0 * n * n);
+            ex.note(launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, stream));
+            prof_end(ex.prof, stream);
+        }
     }
     if (ex.err != hipSuccess) return hip_fail(ex.err, "kernel launch");
     return SW_OK;
@@ -410,6 +430,13 @@ int sw_set_workspace(void* dev_ptr, int64_t bytes)
     return SW_OK;
 }
 
+int sw_set_odd_mode(int mode)
+{
+    if (mode != SW_ODD_PAD && mode != SW_ODD_PEEL) { set_error("unknown mode %d", mode); return SW_EINVAL; }
+    g_odd_mode = mode;
+    return SW_OK;
+}
+
 int sw_set_stream(void* hip_stream)
 {
     g_stream = (hipStream_t)hip_stream;
@@ -481,6 +508,26 @@ int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t
                                     Mat{const_cast<double*>(B), ldb, stride_b}, Mat{C, ldc, stride_c},
                                     (hipStream_t)hip_stream);
     return e == hipSuccess ? SW_OK : hip_fail(e, "sw_leaf_gemm");
+}
+
+int sw_gemm_classical(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, const double* B, int64_t ldb,
+                      double* C, int64_t ldc, int accumulate, void* hip_stream)
+{
+    if (M < 0 || N < 0 || K < 0 || M > 200000 || N > 200000 || K > 200000 || lda < K || ldb < N || ldc < N ||
+        ((M > 0 && N > 0) && (!C || (K > 0 && (!A || !B))))) {
+        set_error("sw_gemm_classical: bad argument");
+        return SW_EINVAL;
+    }
+    if (M == 0 || N == 0) return SW_OK;
+    if (K == 0) {
+        if (accumulate) return SW_OK;
+        hipError_t e = hipMemset2DAsync(C, (size_t)ldc * sizeof(double), 0, (size_t)N * sizeof(double), (size_t)M,
+                                        (hipStream_t)hip_stream);
+        return e == hipSuccess ? SW_OK : hip_fail(e, "sw_gemm_classical");
+    }
+    hipError_t e = launch_gemm(M, N, K, 1, Mat{const_cast<double*>(A), lda, 0}, Mat{const_cast<double*>(B), ldb, 0},
+                               Mat{C, ldc, 0}, accumulate != 0, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SW_OK : hip_fail(e, "sw_gemm_classical");
 }
 
 int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst, int64_t dst_ld,

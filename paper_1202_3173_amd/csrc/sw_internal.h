@@ -76,9 +76,18 @@ struct Mat {
     double* p;
     int64_t ld;
     int64_t stride;
+    bool padded = false;   // one more element behind the end of EVERY row is readable memory of the same buffer
 };
 
-inline Mat quad(const Mat& m, int64_t h, int i, int j) { return Mat{m.p + i * h * m.ld + j * h, m.ld, m.stride}; }
+// Quadrant (i, j) of a batch of 2h x 2h matrices.  Behind a row of a left or top quadrant lies the right
+// quadrant or the next row; only the bottom-right quadrant inherits the question from its parent.
+inline Mat quad(const Mat& m, int64_t h, int i, int j)
+{
+    return Mat{m.p + i * h * m.ld + j * h, m.ld, m.stride, m.padded || !(i == 1 && j == 1)};
+}
+
+// A batch of h x h matrices in the workspace (pitch ws_ld(h), slot ws_mat_elems(h)).
+inline Mat ws_mat(double* p, int64_t h) { return Mat{p, ws_ld(h), ws_mat_elems(h), ws_ld(h) > h}; }
 
 // ---- kernel launchers (each validates nothing: callers pass consistent shapes) --------------------------------
 
@@ -100,7 +109,10 @@ hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t li
 // Zero-padded copy / crop.
 hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst,
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s);
-// Batched classical product on the fp64 matrix cores.
+// Batched classical product on the fp64 matrix cores: C_b = A_b * B_b, all m x m.
 hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s);
+// The same kernel on general shapes: C_b (M x N) = or += A_b (M x K) * B_b (K x N).
+hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, Mat a, Mat b, Mat c, bool accumulate,
+                       hipStream_t s);
 
 }  // namespace sw

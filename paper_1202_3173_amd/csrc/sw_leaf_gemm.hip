@@ -53,6 +53,7 @@ struct GemmArgs {
     int64_t sa, sb, sc;   // batch strides
     int M, N, K;
     int tiles_m, tiles_n;
+    int accumulate;       // 0: C = A*B, 1: C += A*B
 };
 
 template <int VEC>
@@ -293,7 +294,8 @@ leaf_gemm_kernel(const GemmArgs g)
                 double* crow = C + (int64_t)row * g.ldc + n0 + wn * 64 + r16;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (n0 + wn * 64 + j * 16 + r16 < g.N) crow[j * 16] = acc[i][j][v];
+                    if (n0 + wn * 64 + j * 16 + r16 < g.N)
+                        crow[j * 16] = g.accumulate ? crow[j * 16] + acc[i][j][v] : acc[i][j][v];
             }
         }
     }
@@ -303,27 +305,36 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 }  // namespace
 
-hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s)
+hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, Mat a, Mat b, Mat c, bool accumulate,
+                       hipStream_t s)
 {
-    if (m == 0 || batch == 0) return hipSuccess;
+    if (M == 0 || N == 0 || batch == 0) return hipSuccess;
+    if (K == 0) return accumulate ? hipSuccess : hipErrorInvalidValue;   // callers never ask for an empty sum
     // per-thread offsets inside one 128-row panel / 16-row slab are 32-bit element counts
     if (128 * a.ld >= (int64_t)1 << 31 || 16 * b.ld >= (int64_t)1 << 31) return hipErrorInvalidValue;
     GemmArgs g;
     g.A = a.p; g.B = b.p; g.C = c.p;
     g.lda = a.ld; g.ldb = b.ld; g.ldc = c.ld;
     g.sa = a.stride; g.sb = b.stride; g.sc = c.stride;
-    g.M = g.N = g.K = (int)m;
-    g.tiles_m = (int)((m + BM - 1) / BM);
-    g.tiles_n = (int)((m + BN - 1) / BN);
+    g.M = (int)M; g.N = (int)N; g.K = (int)K;
+    g.tiles_m = (int)((M + BM - 1) / BM);
+    g.tiles_n = (int)((N + BN - 1) / BN);
+    g.accumulate = accumulate ? 1 : 0;
     const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * batch;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    // 16-byte loads need aligned pairs; an odd m is fine when every row has padding behind it (the library's
-    // own workspace matrices do), because the pair that straddles the edge then still reads inside the row
+    // 16-byte loads need aligned pairs.  An odd K (pairs along A's rows) or an odd N (pairs along B's rows)
+    // is fine when one more element behind every row is readable memory: the pair that straddles the edge
+    // then stays inside the allocation and its outer half is zeroed (A) or lands in a column never stored (B).
     const bool v2 = aligned16(a.p) && aligned16(b.p) && a.ld % 2 == 0 && b.ld % 2 == 0 && a.stride % 2 == 0 &&
-                    b.stride % 2 == 0 && (m % 2 == 0 || (a.ld > m && b.ld > m));
+                    b.stride % 2 == 0 && (K % 2 == 0 || a.padded) && (N % 2 == 0 || b.padded);
     if (v2) hipLaunchKernelGGL((leaf_gemm_kernel<2>), dim3((unsigned)blocks), dim3(NT), 0, s, g);
     else    hipLaunchKernelGGL((leaf_gemm_kernel<1>), dim3((unsigned)blocks), dim3(NT), 0, s, g);
     return hipGetLastError();
+}
+
+hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s)
+{
+    return launch_gemm(m, m, m, batch, a, b, c, false, s);
 }
 
 }  // namespace sw

@@ -124,6 +124,17 @@ def test_configuration_5(oracle):
     assert s == "DDDBB"
 
 
+def test_peeled_size_near_configuration_5(oracle):
+    # n = 94080 + 17: three more padded matrices would not fit in HBM; peeling needs no copies
+    cfg = dict(inputs.CONFIGS[4], n=94097)
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL)
+    try:
+        s, worst, diff = _check_product(oracle, cfg, "integer", None)
+        assert s == "DDDBB"
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
 def test_configuration_5_integer(oracle):
     cfg = inputs.CONFIGS[4]
     _check_product(oracle, cfg, "integer", None)

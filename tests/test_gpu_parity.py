@@ -204,6 +204,45 @@ def test_product_matches_oracle(oracle, n, levels, schedules, dist):
         assert np.array_equal(run(Ai, Bi, levels, s), exact), s
 
 
+@pytest.mark.parametrize("M,N,K,acc", [(1, 1, 1, False), (130, 5, 70, False), (5, 130, 257, True), (300, 300, 3, True),
+                                        (257, 129, 64, False), (17, 1000, 1000, False), (640, 31, 641, True)])
+def test_classical_product_general_shapes(oracle, M, N, K, acc):
+    # the oracle's classical product is square: embed the rectangular operands in zero-padded squares
+    d = max(M, N, K)
+    A = np.zeros((d, d)); B = np.zeros((d, d))
+    A[:M, :K] = inputs.matrix(d, 31, 0, "uniform")[:M, :K]
+    B[:K, :N] = inputs.matrix(d, 31, 1, "uniform")[:K, :N]
+    ref = oracle.naive(A, B)[:M, :N]
+    C0 = inputs.matrix(d, 32, 0, "uniform")[:M, :N].copy()
+    dA = torch.from_numpy(A[:M, :K].copy()).to(DEV)
+    dB = torch.from_numpy(B[:K, :N].copy()).to(DEV)
+    dC = torch.from_numpy(C0).to(DEV)
+    sw.sw_gemm_classical(M, N, K, dA, K, dB, N, dC, N, accumulate=acc)
+    torch.cuda.synchronize()
+    want = ref + C0 if acc else ref
+    assert np.max(np.abs(dC.cpu().numpy() - want)) <= 1e-10 * max(K, 1)
+    assert np.max(np.abs(dC.cpu().numpy() - want)) <= 8 * K * np.finfo(float).eps
+
+
+@pytest.mark.parametrize("n,levels,schedules", [(1001, 3, ["DBB", "BDD"]), (777, 2, ["BB", "DB"]), (263, 3, ["BBB"]),
+                                                (97, 5, ["DDDBB"]), (1030, 1, ["B", "D"])])
+def test_peeling_matches_oracle(oracle, n, levels, schedules):
+    A = inputs.matrix(n, 4000 + n, 0, "uniform")
+    B = inputs.matrix(n, 4000 + n, 1, "uniform")
+    Ai = inputs.matrix(n, 5000 + n, 0, "integer")
+    Bi = inputs.matrix(n, 5000 + n, 1, "integer")
+    ref = oracle.gemm(A, B, levels)                 # the oracle pads; both approximate the same product
+    exact = (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64)
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL)
+    try:
+        assert sw.sw_plan_memory(n, levels, schedules[0]) == sw.sw_plan_memory(n - n % 2 ** levels, levels, schedules[0])
+        for s in schedules:
+            assert float(np.max(np.abs(run(A, B, levels, s) - ref))) <= tol(n, A, B)
+            assert np.array_equal(run(Ai, Bi, levels, s), exact), s
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
 def test_configuration_2_full_against_oracle(oracle):
     cfg = inputs.CONFIGS[1]
     n, levels = cfg["n"], cfg["levels"]

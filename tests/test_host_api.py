@@ -96,6 +96,19 @@ def test_planner_prefers_bfs_and_puts_dfs_first():
             assert "BD" not in s            # DFS steps first (Limited-Memory shape)
 
 
+def test_peel_mode_needs_no_copies():
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL)
+    try:
+        assert sw.sw_plan_memory(1001, 3, "DDD") == sw.sw_plan_memory(1000, 3, "DDD")
+        assert sw.sw_plan_memory(94097, 5, "DDDBB") == sw.sw_plan_memory(94080, 5, "DDDBB")
+        assert sw.sw_plan_schedule(94097, 5, int(60e9)) == "DDDBB"
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+    assert sw.sw_plan_memory(1001, 3, "DDD") > sw.sw_plan_memory(1008, 3, "DDD")
+    with pytest.raises(sw.SwError):
+        sw.sw_set_odd_mode(7)
+
+
 def test_lm_dfs_step_formula():
     # l = max(0, ceil(log2(4 n / (P^(1/w0) sqrt(M)))))  (Section 3.4), checked inside its validity range
     w0 = math.log2(7)
