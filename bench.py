@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default cfg5, the metric's configuration)")
     ap.add_argument("--schedule", default=None, help="override the step order (default: the configuration's, or the planner's)")
+    ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
+    ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,7 +86,10 @@ def main():
     from paper_1202_3173_amd import binding as sw
     from paper_1202_3173_amd import inputs
 
-    cfg = next(c for c in inputs.CONFIGS if c["name"] == args.config)
+    cfg = dict(next(c for c in inputs.CONFIGS if c["name"] == args.config))
+    if args.n is not None:
+        cfg.update(n=args.n, name=f"{cfg['name']} with n={args.n}", schedule=None)
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL if args.odd_mode == "peel" else sw.SW_ODD_PAD)
     n, levels = cfg["n"], cfg["levels"]
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -126,6 +131,9 @@ def main():
                 "flops_per_launch": leaf["work"] / max(1, leaf["launches"])}
     adds = {}
     add_bytes = add_ms = 0.0
+    if prof["peel"]["launches"]:
+        adds["peel_products"] = {"TFLOPs": round(prof["peel"]["work"] / (prof["peel"]["ms"] * 1e-3) / 1e12, 2),
+                                 "ms_per_step": round(prof["peel"]["ms"] / args.steps, 3)}
     for k in ("pre_add", "post_add", "dfs_add", "pad"):
         p = prof[k]
         if p["launches"]:
@@ -147,11 +155,12 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: n={n} square fp64 C=A*B, {levels} Strassen-Winograd levels, "
-                               f"leaf {n >> levels}, entries {cfg['dist']} seed {cfg['seed']}",
+                               f"leaf {n >> levels}, entries {cfg['dist']} seed {cfg['seed']}"
+                               + (f", odd size handled by {args.odd_mode}" if n % (1 << levels) else ""),
                    "n": n, "levels": levels, "schedule": schedule, "workspace_GB": round(need / 1e9, 3),
                    "hbm_total_GB": round(total_mem / 1e9, 1)},
         "pct_of_fp64_mfma_peak": round(100.0 * eff_gflops / (FP64_MFMA_PEAK_TFLOPS * 1e3), 2),
-        "actual_flops_per_step": sw.sw_flop_count(n, levels),
+        "actual_flops_per_step": sw.sw_flop_count(n, levels) if n % (1 << levels) == 0 else None,
         "roofline": roofline,
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
                       "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds},
