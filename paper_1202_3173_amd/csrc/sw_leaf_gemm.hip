@@ -39,10 +39,7 @@ constexpr int SB = BN + 16;            // LDS pitch of a B k-row (doubles)
 constexpr int A_ELEMS = BM * SA;       // 2304
 constexpr int B_ELEMS = BK * SB;       // 2304
 constexpr int STAGE = A_ELEMS + B_ELEMS;
-#ifndef SW_GROUP_M
-#define SW_GROUP_M 8
-#endif
-constexpr int GROUP_M = SW_GROUP_M;    // tile rows per ordering group
+constexpr int GROUP_M = 8;             // tile rows per ordering group
 constexpr int NUM_XCD = 8;
 
 struct GemmArgs {
@@ -67,11 +64,7 @@ leaf_gemm_kernel(const GemmArgs g)
     const int bid = blockIdx.x;
     const int xcd = bid % NUM_XCD;
     const int per = nb / NUM_XCD, rem = nb % NUM_XCD;
-#ifdef SW_NO_XCD_REMAP
-    const int logical = bid; (void)xcd; (void)per; (void)rem;
-#else
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + bid / NUM_XCD;
-#endif
     const int tpm = g.tiles_m * g.tiles_n;
     const int batch = logical / tpm;
     const int t = logical - batch * tpm;
@@ -197,17 +190,11 @@ leaf_gemm_kernel(const GemmArgs g)
 
     // MFMA tile rows i0 .. i1-1 of one k-step
     auto mfma_rows = [&](int set, int i0, int i1) __attribute__((always_inline)) {
-#ifdef SW_SETPRIO
-        __builtin_amdgcn_s_setprio(1);
-#endif
 #pragma unroll
         for (int i = i0; i < i1; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-#ifdef SW_SETPRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
     };
 #define SW_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -241,10 +228,8 @@ leaf_gemm_kernel(const GemmArgs g)
         SW_FENCE();
         mfma_rows(1, 0, 1);
         SW_FENCE();
-#ifndef SW_EXP_NOLOAD   /* timing experiment only: results are wrong without the loads */
         if (load == 1) { gload(pa, pb); pa += stepA; pb += stepB; }
         if (load == 2) gload_tail((kt + 2) * BK);
-#endif
         SW_FENCE();
         mfma_rows(1, 1, 4);
         SW_FENCE();
@@ -254,9 +239,7 @@ leaf_gemm_kernel(const GemmArgs g)
         mfma_rows(0, 0, 4);
         SW_FENCE();
         // every wavefront has stored the next slab and finished reading this one
-#ifndef SW_EXP_NOBARRIER   /* timing experiment only: LDS contents race without it (addresses stay in bounds) */
         __syncthreads();
-#endif
         // k-step 3, overlapped with the first fragment reads of the next slab
         if (store) fread(cur ^ 1, 0, 0);
         SW_FENCE();
