@@ -98,7 +98,7 @@ def main():
     C = torch.empty((n, n), dtype=torch.float64, device=dev)
     free, total_mem = torch.cuda.mem_get_info()
     schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, int(free - (2 << 30)))
-    need = sw.sw_plan_memory(n, levels, schedule)
+    need = sw.sw_plan_workspace(n, levels, schedule, int(free - (2 << 30)))   # the minimum plus what the library can use
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
 

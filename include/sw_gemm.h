@@ -61,6 +61,13 @@ int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t
  * the all-DFS order (the minimum).  Pure host arithmetic; needs no GPU.  Negative = error code. */
 int64_t sw_plan_memory(int64_t n, int levels, const char* schedule);
 
+/* Bytes of workspace (>= sw_plan_memory, <= budget_bytes) that sw_gemm can make use of for this step order:
+ * with more than the minimum, DFS steps -- deepest first -- keep their four non-trivial T, four S and seven Q
+ * (the storage of a BFS step, Section 3.3.1, without the plain copies) while still solving the seven
+ * subproblems in sequence (Section 3.4), so their additions become the one-pass kernels.  sw_gemm decides the
+ * same way from the size of the workspace it is given.  SW_ENOMEM if the minimum exceeds the budget. */
+int64_t sw_plan_workspace(int64_t n, int levels, const char* schedule, int64_t budget_bytes);
+
 /* Choose the step order for n and levels under a workspace budget: among the orders that fit, the one with
  * the most leaves per batched launch (most BFS steps, placed as deep as possible), DFS steps first among
  * ties (the Limited-Memory scheme of Section 3.4).  out: HOST buffer of levels + 1 chars.  SW_ENOMEM if not

@@ -12,7 +12,7 @@ SW_MAX_LEVELS = 16
 CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel")
 SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
-EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
+EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
 
@@ -39,6 +39,7 @@ def lib():
         "sw_gemm": (ci, [i64, vp, vp, vp, ci, cp]),
         "sw_gemm_ex": (ci, [i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
         "sw_plan_memory": (i64, [i64, ci, cp]),
+        "sw_plan_workspace": (i64, [i64, ci, cp, i64]),
         "sw_plan_schedule": (ci, [i64, ci, i64, ctypes.c_char_p]),
         "sw_model_words": (i64, [i64, ci, cp]),
         "sw_lm_dfs_steps": (ci, [dbl, dbl, dbl]),
@@ -94,6 +95,10 @@ def _f64_cuda(t, name):
 
 def sw_plan_memory(n, levels, schedule=None):
     return _check(lib().sw_plan_memory(n, levels, _sched(schedule)))
+
+
+def sw_plan_workspace(n, levels, schedule, budget_bytes):
+    return _check(lib().sw_plan_workspace(n, levels, _sched(schedule), budget_bytes))
 
 
 def sw_plan_schedule(n, levels, budget_bytes):

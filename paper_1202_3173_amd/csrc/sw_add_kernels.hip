@@ -52,17 +52,20 @@ __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 // ---- BFS pre-additions ------------------------------------------------------------------------------------
 // SIDE 0: T0 = A11, T1 = A12, T2 = A21 + A22, T3 = T2 - A11, T4 = A11 - A21, T5 = A12 - T3, T6 = A22
 // SIDE 1: S0 = B11, S1 = B21, S2 = B12 - B11, S3 = B22 - S2, S4 = B22 - B12, S5 = B22, S6 = S3 - B21
+// copies != 0: all seven operands are written, child j of parent p in slot 7p + j.  copies == 0: only the four
+// that need arithmetic (T2, T3, T4, T5 or S2, S3, S4, S6) are written, to slots 4p + 0..3; the plain quadrants
+// are then used in place by the caller.
 template <int SIDE, int VEC>
 __global__ void __launch_bounds__(NT)
 pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int h,
-               double* __restrict__ child, int64_t cld, int64_t cstride)
+               double* __restrict__ child, int64_t cld, int64_t cstride, int copies)
 {
     typedef typename VecT<VEC>::type V;
     const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
     if (cx >= h) return;
     const int r0 = blockIdx.y * ROWS;
     const double* P = parent + (int64_t)blockIdx.z * pstride;
-    double* O = child + (int64_t)blockIdx.z * 7 * cstride;
+    double* O = child + (int64_t)blockIdx.z * (copies ? 7 : 4) * cstride;
 
     V q11[ROWS], q12[ROWS], q21[ROWS], q22[ROWS];
 #pragma unroll
@@ -87,25 +90,35 @@ pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, 
                 const V t3 = t2 - q11[r];
                 const V t4 = q11[r] - q21[r];
                 const V t5 = q12[r] - t3;
-                st<VEC>(o, q11[r]);
-                st<VEC>(o + cstride, q12[r]);
-                st<VEC>(o + 2 * cstride, t2);
-                st<VEC>(o + 3 * cstride, t3);
-                st<VEC>(o + 4 * cstride, t4);
-                st<VEC>(o + 5 * cstride, t5);
-                st<VEC>(o + 6 * cstride, q22[r]);
+                if (copies) {
+                    st<VEC>(o, q11[r]);
+                    st<VEC>(o + cstride, q12[r]);
+                    st<VEC>(o + 6 * cstride, q22[r]);
+                    o += 2 * cstride;
+                }
+                st<VEC>(o, t2);
+                st<VEC>(o + cstride, t3);
+                st<VEC>(o + 2 * cstride, t4);
+                st<VEC>(o + 3 * cstride, t5);
             } else {
                 const V s2 = q12[r] - q11[r];
                 const V s3 = q22[r] - s2;
                 const V s4 = q22[r] - q12[r];
                 const V s6 = s3 - q21[r];
-                st<VEC>(o, q11[r]);
-                st<VEC>(o + cstride, q21[r]);
-                st<VEC>(o + 2 * cstride, s2);
-                st<VEC>(o + 3 * cstride, s3);
-                st<VEC>(o + 4 * cstride, s4);
-                st<VEC>(o + 5 * cstride, q22[r]);
-                st<VEC>(o + 6 * cstride, s6);
+                if (copies) {
+                    st<VEC>(o, q11[r]);
+                    st<VEC>(o + cstride, q21[r]);
+                    st<VEC>(o + 2 * cstride, s2);
+                    st<VEC>(o + 3 * cstride, s3);
+                    st<VEC>(o + 4 * cstride, s4);
+                    st<VEC>(o + 5 * cstride, q22[r]);
+                    st<VEC>(o + 6 * cstride, s6);
+                } else {
+                    st<VEC>(o, s2);
+                    st<VEC>(o + cstride, s3);
+                    st<VEC>(o + 2 * cstride, s4);
+                    st<VEC>(o + 3 * cstride, s6);
+                }
             }
         }
     }
@@ -382,14 +395,14 @@ inline dim3 grid_for(int64_t h, int vec, int rows, int64_t batch)
 
 }  // namespace
 
-hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, hipStream_t s)
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s)
 {
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(child);
     const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                              \
     hipLaunchKernelGGL((pre_add_kernel<SIDE, VEC>), g, dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
-                       (int)h, child.p, child.ld, child.stride)
+                       (int)h, child.p, child.ld, child.stride, copies ? 1 : 0)
     if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
     else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
 #undef SW_LAUNCH

@@ -151,6 +151,7 @@ struct Exec {
     int64_t used = 0;
     const char* sched;
     int levels;
+    uint32_t rich = 0;      // DFS levels that keep BFS-style storage (choose_rich)
     Profiler* prof;
     hipError_t err = hipSuccess;
 
@@ -213,12 +214,32 @@ struct Exec {
             // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
             Mat T = ws_mat(take(7 * live * e), h), S = ws_mat(take(7 * live * e), h), Q = ws_mat(take(7 * live * e), h);
             prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
-            note(launch_pre_add(0, A, live, h, T, stream));
+            note(launch_pre_add(0, A, live, h, T, true, stream));
             prof_end(prof, stream);
             prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
-            note(launch_pre_add(1, B, live, h, S, stream));
+            note(launch_pre_add(1, B, live, h, S, true, stream));
             prof_end(prof, stream);
             mul(T, S, Q, h, level + 1, 7 * live);
+            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, h, 7, 4));
+            note(launch_post_add(Q, live, h, C, stream));
+            prof_end(prof, stream);
+        } else if (rich & (1u << level)) {
+            // DFS step with the storage of a BFS step: the four non-trivial T, four S and seven Q of every
+            // parent are kept, so the additions are the one-pass BFS kernels (27 instead of 38 half-size
+            // matrices moved per parent), but the seven subproblems are still solved in sequence.
+            Mat Tn = ws_mat(take(4 * live * e), h), Sn = ws_mat(take(4 * live * e), h), Q = ws_mat(take(7 * live * e), h);
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4));
+            note(launch_pre_add(0, A, live, h, Tn, false, stream));
+            prof_end(prof, stream);
+            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4));
+            note(launch_pre_add(1, B, live, h, Sn, false, stream));
+            prof_end(prof, stream);
+            auto slot = [&](const Mat& base, int k, int per) { return Mat{base.p + k * e, base.ld, per * e, base.padded}; };
+            const Mat Ta[7] = {quad(A, h, 0, 0), quad(A, h, 0, 1), slot(Tn, 0, 4), slot(Tn, 1, 4), slot(Tn, 2, 4),
+                               slot(Tn, 3, 4), quad(A, h, 1, 1)};
+            const Mat Sb[7] = {quad(B, h, 0, 0), quad(B, h, 1, 0), slot(Sn, 0, 4), slot(Sn, 1, 4), slot(Sn, 2, 4),
+                               quad(B, h, 1, 1), slot(Sn, 3, 4)};
+            for (int j = 0; j < 7; ++j) mul(Ta[j], Sb[j], slot(Q, j, 7), h, level + 1, live);
             prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, h, 7, 4));
             note(launch_post_add(Q, live, h, C, stream));
             prof_end(prof, stream);
@@ -302,6 +323,13 @@ static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, i
     ex.ws_bytes = ws_bytes;
     ex.sched = schedule;
     ex.levels = levels;
+    {
+        // spend what the workspace has beyond the minimum on the rich form of the deepest DFS steps
+        const int64_t q = (int64_t)1 << levels;
+        const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
+        const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
+        ex.rich = choose_rich(nrec, levels, schedule, ws_bytes - fixed);
+    }
     ex.prof = profiler();
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
@@ -374,6 +402,24 @@ int64_t sw_plan_memory(int64_t n, int levels, const char* schedule)
         return SW_EINVAL;
     }
     return total_need(n, levels, s.c_str());
+}
+
+int64_t sw_plan_workspace(int64_t n, int levels, const char* schedule, int64_t budget_bytes)
+{
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    if (!schedule || !schedule_ok(schedule, levels)) { set_error("bad schedule"); return SW_EINVAL; }
+    const int64_t need = total_need(n, levels, schedule);
+    if (need > budget_bytes) {
+        set_error("schedule %s needs %lld bytes, budget is %lld", schedule, (long long)need, (long long)budget_bytes);
+        return SW_ENOMEM;
+    }
+    if (n == 0) return 0;
+    const int64_t q = (int64_t)1 << levels;
+    const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
+    const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
+    const uint32_t rich = choose_rich(nrec, levels, schedule, budget_bytes - fixed);
+    return fixed + ws_need_bytes(nrec, schedule, 1, rich);
 }
 
 int sw_plan_schedule(int64_t n, int levels, int64_t budget_bytes, char* out)
@@ -457,7 +503,7 @@ int sw_pre_add(int side, const double* parent, int64_t parent_ld, int64_t parent
         return SW_EINVAL;
     }
     hipError_t e = launch_pre_add(side, Mat{const_cast<double*>(parent), parent_ld, parent_stride}, live, h,
-                                  Mat{child, child_ld, child_stride}, (hipStream_t)hip_stream);
+                                  Mat{child, child_ld, child_stride}, true, (hipStream_t)hip_stream);
     return e == hipSuccess ? SW_OK : hip_fail(e, "sw_pre_add");
 }
 

@@ -39,17 +39,30 @@ inline bool fuse_two_bfs(const char* sched)
 // parent (Section 3.3.1), or for all 49 grandchildren when two BFS steps are fused; DFS step: two
 // temporaries per parent, because products are written straight into the parent's C quadrants (the footnote
 // of Section 3.3.1 allows a few temporaries).
-inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live)
+//
+// rich: bit i set = the DFS step at level `level + i` keeps its four non-trivial T, four S and seven Q (15
+// buffers per parent, the storage of a BFS step without the plain copies) while still solving the seven
+// subproblems in sequence; its additions are then the one-pass BFS kernels.  0 = the minimum.
+inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live, uint32_t rich = 0)
 {
     if (*sched == '\0') return 0;
     const int64_t h = n / 2;
     const int64_t e = ws_mat_elems(h) * (int64_t)sizeof(double);
     if (fuse_two_bfs(sched)) {
         const int64_t e4 = ws_mat_elems(h / 2) * (int64_t)sizeof(double);
-        return 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live);
+        return 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live, rich >> 2);
     }
-    if (*sched == 'B') return 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live);
-    return 2 * live * e + ws_need_bytes(h, sched + 1, live);
+    if (*sched == 'B') return 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live, rich >> 1);
+    return ((rich & 1u) ? 15 : 2) * live * e + ws_need_bytes(h, sched + 1, live, rich >> 1);
+}
+
+// Which DFS steps get the rich form for a workspace of `budget` bytes: deepest first, while it fits.
+inline uint32_t choose_rich(int64_t n, int levels, const char* sched, int64_t budget)
+{
+    uint32_t rich = 0;
+    for (int i = levels - 1; i >= 0; --i)
+        if (sched[i] == 'D' && ws_need_bytes(n, sched, 1, rich | (1u << i)) <= budget) rich |= 1u << i;
+    return rich;
 }
 
 inline int64_t padded_n(int64_t n, int levels)
@@ -92,7 +105,8 @@ inline Mat ws_mat(double* p, int64_t h) { return Mat{p, ws_ld(h), ws_mat_elems(h
 // ---- kernel launchers (each validates nothing: callers pass consistent shapes) --------------------------------
 
 // BFS pre-additions, Appendix A columns 1 (side 0, T from A) and 2 (side 1, S from B).
-hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, hipStream_t s);
+// copies: write all seven operands (slot 7p + j); otherwise only the four non-trivial ones (slot 4p + 0..3).
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s);
 // BFS post-additions, Appendix A column 4.
 hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s);
 // Two consecutive BFS steps in one pass: parent of size 4m -> 49 grandchildren of size m, and back.

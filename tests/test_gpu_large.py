@@ -51,8 +51,8 @@ def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=24):
     free, _ = torch.cuda.mem_get_info()
     if schedule is None:
         schedule = sw.sw_plan_schedule(n, levels, int(free - (2 << 30)))
-    need = sw.sw_plan_memory(n, levels, schedule)
-    assert need <= free, f"schedule {schedule} needs {need} bytes, {free} free"
+    need = sw.sw_plan_workspace(n, levels, schedule, int(free - (2 << 30)))   # as bench.py does
+    assert sw.sw_plan_memory(n, levels, schedule) <= need <= free, f"schedule {schedule} needs {need} bytes, {free} free"
     ws = torch.empty(need, dtype=torch.uint8, device=DEV)
     sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, ws)
     torch.cuda.synchronize()

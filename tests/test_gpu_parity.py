@@ -243,6 +243,31 @@ def test_peeling_matches_oracle(oracle, n, levels, schedules):
         sw.sw_set_odd_mode(sw.SW_ODD_PAD)
 
 
+@pytest.mark.parametrize("n,levels,sched", [(512, 2, "DD"), (1000, 3, "DBD"), (1200, 4, "DDBB"), (96, 5, "BDBDB"), (777, 2, "DB")])
+def test_dfs_steps_with_bfs_storage_give_the_same_bits(oracle, n, levels, sched):
+    # with workspace beyond the minimum, DFS steps keep T, S, Q and use the one-pass addition kernels
+    A = inputs.matrix(n, 6000 + n, 0, "uniform")
+    B = inputs.matrix(n, 6000 + n, 1, "uniform")
+    lean = run(A, B, levels, sched)
+    assert float(np.max(np.abs(lean - oracle.gemm(A, B, levels)))) <= tol(n, A, B)
+    need = sw.sw_plan_memory(n, levels, sched)
+    full = sw.sw_plan_workspace(n, levels, sched, 10 ** 11)
+    assert full > need
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    results = []
+    for nbytes in sorted({full, (need + full) // 2 // 256 * 256}):
+        C = torch.full((n, n), float("nan"), dtype=torch.float64, device=DEV)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        sw.sw_profile_enable(True)
+        sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, sched, ws)
+        torch.cuda.synchronize()
+        prof = sw.sw_profile_read()
+        sw.sw_profile_enable(False)
+        assert np.array_equal(C.cpu().numpy(), lean), nbytes
+        results.append(prof["dfs_add"]["launches"])
+    assert results[-1] == 0          # every DFS step in its rich form: no element-wise DFS kernels left
+
+
 def test_configuration_2_full_against_oracle(oracle):
     cfg = inputs.CONFIGS[1]
     n, levels = cfg["n"], cfg["levels"]

@@ -96,6 +96,30 @@ def test_planner_prefers_bfs_and_puts_dfs_first():
             assert "BD" not in s            # DFS steps first (Limited-Memory shape)
 
 
+def test_plan_workspace_spends_extra_memory_on_the_deepest_dfs_steps():
+    def elems(h):
+        ld = (h + 15) // 16 * 16
+        if ld >= 256 and ld % 256 == 0:
+            ld += 16
+        return (ld * h + 31) // 32 * 32
+    n, L, s = 1024, 3, "DDD"
+    lean = sw.sw_plan_memory(n, L, s)
+    assert lean == (2 * elems(512) + 2 * elems(256) + 2 * elems(128)) * 8
+    assert sw.sw_plan_workspace(n, L, s, lean) == lean
+    assert sw.sw_plan_workspace(n, L, s, lean + 13 * elems(128) * 8) == lean + 13 * elems(128) * 8     # deepest step rich
+    assert sw.sw_plan_workspace(n, L, s, lean + 13 * elems(128) * 8 + 100) == lean + 13 * elems(128) * 8
+    assert sw.sw_plan_workspace(n, L, s, 10 ** 10) == (15 * elems(512) + 15 * elems(256) + 15 * elems(128)) * 8
+    assert sw.sw_plan_workspace(n, L, "BBB", 10 ** 10) == sw.sw_plan_memory(n, L, "BBB")               # nothing to upgrade
+    with pytest.raises(sw.SwError) as e:
+        sw.sw_plan_workspace(n, L, s, lean - 1)
+    assert e.value.code == sw.SW_ENOMEM
+    # configuration 5: the level-2 DFS step (49 nodes of 23520) is the one that fits in what 288 GiB leave
+    n5 = 94080
+    left = 288 * 2 ** 30 - 3 * n5 * n5 * 8 - 4 * 2 ** 30
+    got = sw.sw_plan_workspace(n5, 5, "DDDBB", left)
+    assert got == sw.sw_plan_memory(n5, 5, "DDDBB") + 13 * elems(11760) * 8
+
+
 def test_peel_mode_needs_no_copies():
     sw.sw_set_odd_mode(sw.SW_ODD_PEEL)
     try:
