@@ -52,6 +52,18 @@ int sw_gemm(int64_t n, const double* A, const double* B, double* C, int levels, 
 int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* The product with diagonal scaling (Section 6.1): D1 C D3 = (D1 A D2)(D2^-1 B D3) with D1, D2, D3 diagonal
+ * powers of two (scaling and unscaling are exact).  scaling: SW_SCALE_OUTSIDE (D1, D3: every row of A and
+ * column of B gets a largest entry in [1, 2); the error of entry (i, j) then relates to ||A(i,:)|| ||B(:,j)||
+ * instead of ||A|| ||B||), SW_SCALE_INSIDE (D2: column k of A and row k of B get largest entries of equal
+ * size), or both (outside first); 0 = plain sw_gemm.  A and B stay untouched: scaled copies live in the
+ * workspace, which must hold sw_plan_memory_scaled(n, levels, schedule) bytes.  Same state and rules as sw_gemm. */
+#define SW_SCALE_OUTSIDE 1
+#define SW_SCALE_INSIDE 2
+int sw_gemm_scaled(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule,
+                   int scaling);
+int64_t sw_plan_memory_scaled(int64_t n, int levels, const char* schedule);
+
 /* ---- the planner (Section 3.1: pick the step order that uses the memory there is; Sections 3.3.1, 3.4.1) - */
 
 /* Bytes of workspace sw_gemm needs beyond A, B, C for this n, depth and step order (what THIS library
@@ -152,7 +164,8 @@ int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
 #define SW_CLASS_DFS_ADD 3  /* element-wise kernels of DFS steps        */
 #define SW_CLASS_PAD 4      /* pad / crop copies                        */
 #define SW_CLASS_PEEL 5     /* thin classical products of peeling (work = flops) */
-#define SW_NUM_CLASSES 6
+#define SW_CLASS_SCALE 6    /* diagonal scaling: maxima, scaled copies, unscaling */
+#define SW_NUM_CLASSES 7
 
 /* on != 0: bracket every kernel launch of sw_gemm with HIP events on the launch stream (no host sync).
  * sw_profile_read synchronises those events, adds up per class the elapsed milliseconds, the launches and

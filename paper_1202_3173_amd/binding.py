@@ -9,10 +9,11 @@ LIB_PATH = os.environ.get("SW_GEMM_LIB") or os.path.join(_HERE, "libsw_gemm.so")
 
 SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
 SW_MAX_LEVELS = 16
-CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel")
+CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel", "scale")
+SW_SCALE_OUTSIDE, SW_SCALE_INSIDE = 1, 2
 SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
-EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
+EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
 
@@ -39,6 +40,8 @@ def lib():
         "sw_gemm": (ci, [i64, vp, vp, vp, ci, cp]),
         "sw_gemm_ex": (ci, [i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
         "sw_plan_memory": (i64, [i64, ci, cp]),
+        "sw_gemm_scaled": (ci, [i64, vp, vp, vp, ci, cp, ci]),
+        "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
         "sw_plan_workspace": (i64, [i64, ci, cp, i64]),
         "sw_plan_schedule": (ci, [i64, ci, i64, ctypes.c_char_p]),
         "sw_model_words": (i64, [i64, ci, cp]),
@@ -155,6 +158,19 @@ def sw_gemm(n, A, B, C, levels, schedule=None):
         if not t.is_contiguous() or tuple(t.shape) != (n, n):
             raise ValueError(f"{name} must be a contiguous {n} x {n} tensor")
     return _check(lib().sw_gemm(n, _ptr(A), _ptr(B), _ptr(C), levels, _sched(schedule)))
+
+
+def sw_gemm_scaled(n, A, B, C, levels, schedule, scaling):
+    """C = A @ B with diagonal scaling (Section 6.1) through the library state (workspace, stream)."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+        if not t.is_contiguous() or tuple(t.shape) != (n, n):
+            raise ValueError(f"{name} must be a contiguous {n} x {n} tensor")
+    return _check(lib().sw_gemm_scaled(n, _ptr(A), _ptr(B), _ptr(C), levels, _sched(schedule), scaling))
+
+
+def sw_plan_memory_scaled(n, levels, schedule=None):
+    return _check(lib().sw_plan_memory_scaled(n, levels, _sched(schedule)))
 
 
 def sw_gemm_ex(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, stream_handle=None):

@@ -392,6 +392,82 @@ int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t
     return gemm_impl(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+// ---- diagonal scaling around the product (Section 6.1) ------------------------------------------------------
+
+static int64_t scaled_extra_bytes(int64_t n)
+{
+    // scaled copies of A and B, and seven vectors (row/column maxima and D1, D2, 1/D2, D3)
+    return 2 * ws_mat_elems(n) * (int64_t)sizeof(double) + 7 * ((n + 31) / 32 * 32) * (int64_t)sizeof(double);
+}
+
+int64_t sw_plan_memory_scaled(int64_t n, int levels, const char* schedule)
+{
+    const int64_t base = sw_plan_memory(n, levels, schedule);
+    return base < 0 ? base : base + scaled_extra_bytes(n);
+}
+
+int sw_gemm_scaled(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule,
+                   int scaling)
+{
+    if (scaling < 0 || scaling > (SW_SCALE_OUTSIDE | SW_SCALE_INSIDE)) { set_error("unknown scaling %d", scaling); return SW_EINVAL; }
+    if (scaling == 0) return sw_gemm(n, A, B, C, levels, schedule);
+    int rc = check_shape(n, levels);
+    if (rc != SW_OK) return rc;
+    if (n == 0) return SW_OK;
+    if (!A || !B || !C) { set_error("NULL matrix pointer"); return SW_EINVAL; }
+    if (overlaps(C, n * n, A, n * n) || overlaps(C, n * n, B, n * n)) { set_error("C overlaps A or B"); return SW_EINVAL; }
+    const int64_t extra = scaled_extra_bytes(n);
+    if (!g_ws || g_ws_bytes < extra) {
+        set_error("workspace of %lld bytes is too small for the scaled copies (%lld)", (long long)g_ws_bytes, (long long)extra);
+        return SW_ENOMEM;
+    }
+    if (overlaps((const double*)g_ws, extra / 8, A, n * n) || overlaps((const double*)g_ws, extra / 8, B, n * n) ||
+        overlaps((const double*)g_ws, extra / 8, C, n * n)) {
+        set_error("workspace overlaps A, B or C");
+        return SW_EINVAL;
+    }
+    hipStream_t st = g_stream;
+    char* w = (char*)g_ws;
+    const int64_t ld = ws_ld(n), e = ws_mat_elems(n), nv = (n + 31) / 32 * 32;
+    double* As = (double*)w;
+    double* Bs = As + e;
+    double* vec = Bs + e;
+    double *ma = vec, *mb = vec + nv, *d1 = vec + 2 * nv, *d3 = vec + 3 * nv, *d2 = vec + 4 * nv, *d2i = vec + 5 * nv,
+           *tmp = vec + 6 * nv;
+    hipError_t err = hipSuccess;
+    auto note = [&](hipError_t x) { if (err == hipSuccess && x != hipSuccess) err = x; };
+    const bool outside = scaling & SW_SCALE_OUTSIDE, inside = scaling & SW_SCALE_INSIDE;
+    Profiler* prof = profiler();
+    prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * (outside ? 2.0 : 0.0) + 8.0 * n * n * (inside ? 2.0 : 0.0) + 8.0 * n * n * 4.0);
+    if (outside) {
+        note(launch_absmax_rows(A, n, n, nullptr, ma, st));            // max_j |A_ij|
+        note(launch_outside_scale(ma, n, d1, st));
+        note(launch_absmax_cols(B, n, n, nullptr, mb, st));            // max_i |B_ij|
+        note(launch_outside_scale(mb, n, d3, st));
+    }
+    if (inside) {
+        note(launch_absmax_cols(A, n, n, outside ? d1 : nullptr, ma, st));   // max_i D1_ii |A_ik|
+        note(launch_absmax_rows(B, n, n, outside ? d3 : nullptr, tmp, st));  // max_j |B_kj| D3_jj
+        note(launch_inside_scale(ma, tmp, n, d2, d2i, st));
+    }
+    note(launch_scale_copy(A, n, n, outside ? d1 : nullptr, inside ? d2 : nullptr, As, ld, st));    // D1 A D2
+    note(launch_scale_copy(B, n, n, inside ? d2i : nullptr, outside ? d3 : nullptr, Bs, ld, st));   // D2^-1 B D3
+    prof_end(prof, st);
+    if (err != hipSuccess) return hip_fail(err, "scaling kernels");
+    rc = gemm_impl(n, As, ld, Bs, ld, C, n, levels, schedule, w + extra, g_ws_bytes - extra, st);
+    if (rc != SW_OK) return rc;
+    if (outside) {
+        // C = D1^-1 C' D3^-1: the reciprocals of powers of two are formed exactly
+        prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * 2.0);
+        note(launch_outside_scale(d1, n, ma, st));     // 2^-e(2^-k) = 2^k: reuses the exponent kernel to invert
+        note(launch_outside_scale(d3, n, mb, st));
+        note(launch_scale_copy(C, n, n, ma, mb, C, n, st));
+        prof_end(prof, st);
+        if (err != hipSuccess) return hip_fail(err, "unscaling kernels");
+    }
+    return SW_OK;
+}
+
 int64_t sw_plan_memory(int64_t n, int levels, const char* schedule)
 {
     int rc = check_shape(n, levels);
@@ -567,8 +643,7 @@ int sw_gemm_classical(int64_t M, int64_t N, int64_t K, const double* A, int64_t 
     if (M == 0 || N == 0) return SW_OK;
     if (K == 0) {
         if (accumulate) return SW_OK;
-        hipError_t e = hipMemset2DAsync(C, (size_t)ldc * sizeof(double), 0, (size_t)N * sizeof(double), (size_t)M,
-                                        (hipStream_t)hip_stream);
+        hipError_t e = launch_pad_copy(C, ldc, 0, 0, C, ldc, M, N, (hipStream_t)hip_stream);   // an empty sum: zeros
         return e == hipSuccess ? SW_OK : hip_fail(e, "sw_gemm_classical");
     }
     hipError_t e = launch_gemm(M, N, K, 1, Mat{const_cast<double*>(A), lda, 0}, Mat{const_cast<double*>(B), ldb, 0},

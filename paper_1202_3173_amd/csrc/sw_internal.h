@@ -129,4 +129,12 @@ hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipSt
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, Mat a, Mat b, Mat c, bool accumulate,
                        hipStream_t s);
 
+// Diagonal scaling (Section 6.1): weighted maxima of |X| over rows / columns, scale vectors, scaled copy.
+hipError_t launch_absmax_rows(const double* X, int64_t ld, int64_t n, const double* w, double* out, hipStream_t s);
+hipError_t launch_absmax_cols(const double* X, int64_t ld, int64_t n, const double* w, double* out, hipStream_t s);
+hipError_t launch_outside_scale(const double* m, int64_t n, double* sc, hipStream_t s);
+hipError_t launch_inside_scale(const double* a, const double* b, int64_t n, double* d, double* dinv, hipStream_t s);
+hipError_t launch_scale_copy(const double* X, int64_t xld, int64_t n, const double* r, const double* c, double* Y,
+                             int64_t yld, hipStream_t s);
+
 }  // namespace sw

@@ -17,6 +17,10 @@ distributions
     "uniform"    2u - 1                                   iid U[-1, 1)
     "rowscaled"  (2u - 1) * (1 + row / n)                 row-dependent magnitude
     "integer"    ((z >> 32) * 17 >> 32) - 8               iid integers in [-8, 8]
+    "badscaled"  (2u - 1) * 2^(s(row) + g(col)) for A and (2u - 1) * 2^(-g(row) + t(col)) for B, with
+                 s(i) = round(40 i / n) - 20, t(j) = 20 - round(40 j / n), g(k) = round(30 k / n) - 15:
+                 rows of A, columns of B and the inner index span many binades (the case for the
+                 diagonal scaling of Section 6.1); host only
     "normal"     sqrt(-2 ln u1) * cos(2 pi u2) with u1 = ((z1 >> 11) + 1) * 2^-53 and
                  u2 from counters 2*idx and 2*idx + 1     iid N(0, 1); host only
 
@@ -35,7 +39,7 @@ GAMMA = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
 
-DISTS = ("uniform", "rowscaled", "integer", "normal")
+DISTS = ("uniform", "rowscaled", "integer", "normal", "badscaled")
 
 # The five workloads of the build's baseline file (shape, depth, step order, distribution, seed).
 CONFIGS = [
@@ -89,6 +93,14 @@ def block(n, seed, which, dist, rows, cols):
         v = 2.0 * u - 1.0
         if dist == "rowscaled":
             v = v * (1.0 + rows.astype(np.float64) / float(n))
+        if dist == "badscaled":
+            r = rows.astype(np.float64)
+            c = cols.astype(np.float64)
+            g = lambda k: np.round(30.0 * k / n) - 15.0
+            if which == 0:
+                v = v * np.exp2((np.round(40.0 * r / n) - 20.0) + g(c))
+            else:
+                v = v * np.exp2(-g(r) + (20.0 - np.round(40.0 * c / n)))
         return v
 
 
