@@ -75,6 +75,7 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default cfg5, the metric's configuration)")
     ap.add_argument("--schedule", default=None, help="override the step order (default: the configuration's, or the planner's)")
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
+    ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -89,6 +90,8 @@ def main():
     cfg = dict(next(c for c in inputs.CONFIGS if c["name"] == args.config))
     if args.n is not None:
         cfg.update(n=args.n, name=f"{cfg['name']} with n={args.n}", schedule=None)
+    if args.levels is not None:
+        cfg.update(levels=args.levels, name=f"{cfg['name']} with levels={args.levels}", schedule=None)
     sw.sw_set_odd_mode(sw.SW_ODD_PEEL if args.odd_mode == "peel" else sw.SW_ODD_PAD)
     n, levels = cfg["n"], cfg["levels"]
     dev = "cuda:0"
@@ -98,6 +101,8 @@ def main():
     C = torch.empty((n, n), dtype=torch.float64, device=dev)
     free, total_mem = torch.cuda.mem_get_info()
     schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, int(free - (2 << 30)))
+    if levels == 0:
+        schedule = ""
     need = sw.sw_plan_workspace(n, levels, schedule, int(free - (2 << 30)))   # the minimum plus what the library can use
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
