@@ -321,6 +321,34 @@ def test_side_stream_and_profile_record(oracle):
     assert all(v["ms"] > 0 for k, v in prof.items() if v["launches"])
 
 
+def test_product_can_be_captured_in_a_hip_graph_and_replayed(oracle):
+    # the library allocates nothing, records no memset and never synchronises, so a caller may capture it;
+    # every replay, with eager work of the program in between, must reproduce the eager result
+    n, levels, sched = 320, 3, "DBB"
+    A = inputs.matrix(n, 61, 0, "uniform")
+    B = inputs.matrix(n, 61, 1, "uniform")
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.empty_like(dA)
+    ws = torch.empty(sw.sw_plan_workspace(n, levels, sched, 10 ** 9), dtype=torch.uint8, device=DEV)
+    sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, sched, ws)
+    torch.cuda.synchronize()
+    eager = C.clone()
+    assert float(np.max(np.abs(eager.cpu().numpy() - oracle.gemm(A, B, levels)))) <= tol(n, A, B)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, sched, ws)       # launches go to the capturing stream
+    other = torch.from_numpy(inputs.matrix(n, 62, 0, "uniform")).to(DEV)
+    for rep in range(4):
+        C.fill_(float("nan"))
+        ws.random_(0, 255)                                            # workspace contents must not matter
+        scratch = other @ other                                       # unrelated eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, eager), rep
+        assert torch.isfinite(scratch).all()
+
+
 def test_argument_errors_on_device():
     n = 64
     A = torch.zeros((n, n), dtype=torch.float64, device=DEV)
