@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
+    ap.add_argument("--overlap", type=int, default=None, help="0: one stream; k > 0: three streams, addition kernels capped at k workgroups")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,6 +94,8 @@ def main():
     if args.levels is not None:
         cfg.update(levels=args.levels, name=f"{cfg['name']} with levels={args.levels}", schedule=None)
     sw.sw_set_odd_mode(sw.SW_ODD_PEEL if args.odd_mode == "peel" else sw.SW_ODD_PAD)
+    if args.overlap is not None:
+        sw.sw_set_overlap(args.overlap)
     n, levels = cfg["n"], cfg["levels"]
     dev = "cuda:0"
     torch.cuda.set_device(0)

@@ -74,7 +74,9 @@ int64_t sw_plan_memory_scaled(int64_t n, int levels, const char* schedule);
 int64_t sw_plan_memory(int64_t n, int levels, const char* schedule);
 
 /* Bytes of workspace (>= sw_plan_memory, <= budget_bytes) that sw_gemm can make use of for this step order:
- * with more than the minimum, DFS steps -- deepest first -- keep their four non-trivial T, four S and seven Q
+ * with more than the minimum, first the buffers next to the leaves exist twice (consecutive leaf launches
+ * alternate, so additions overlap products; only with sw_set_overlap on and a DFS step above), then DFS steps
+ * -- deepest first -- keep their four non-trivial T, four S and seven Q
  * (the storage of a BFS step, Section 3.3.1, without the plain copies) while still solving the seven
  * subproblems in sequence (Section 3.4), so their additions become the one-pass kernels.  sw_gemm decides the
  * same way from the size of the workspace it is given.  SW_ENOMEM if the minimum exceeds the budget. */
@@ -103,6 +105,15 @@ double sw_flop_count(int64_t n, int levels);
 
 int sw_set_workspace(void* dev_ptr, int64_t bytes); /* caller-owned; NULL/0 clears it                    */
 int sw_set_stream(void* hip_stream);                /* hipStream_t; NULL = the null stream               */
+
+/* on != 0 (default): inside one product the kernels that form operands, the leaf products and the kernels
+ * that fold products into C run on three streams (the caller's and two of the library's), ordered by events
+ * from the address ranges each kernel reads and writes, so HBM-bound additions overlap MFMA-bound products;
+ * towards the caller the call still behaves as if everything ran on the caller's stream.  on == 0: one
+ * stream.  The results are the same bits either way.  While overlapping, each addition kernel is launched as
+ * a persistent streaming kernel of at most `on` workgroups (on == 1: the default of 256, one per CU), so that
+ * it takes little of each CU away from the leaf products running beside it. */
+int sw_set_overlap(int on);
 
 /* What sw_gemm, sw_plan_memory and sw_plan_schedule do when 2^levels does not divide n (Section 3.1:
  * "padding or dynamic peeling").  SW_ODD_PAD (default): zero-padded workspace copies of A, B, C of the next

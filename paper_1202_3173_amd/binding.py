@@ -14,7 +14,7 @@ SW_SCALE_OUTSIDE, SW_SCALE_INSIDE = 1, 2
 SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
-           "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
+           "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
 
 
@@ -50,6 +50,7 @@ def lib():
         "sw_set_workspace": (ci, [vp, i64]),
         "sw_set_stream": (ci, [vp]),
         "sw_set_odd_mode": (ci, [ci]),
+        "sw_set_overlap": (ci, [ci]),
         "sw_gemm_classical": (ci, [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]),
         "sw_last_error": (cp, []),
         "sw_pre_add": (ci, [ci, vp, i64, i64, i64, i64, vp, i64, i64, vp]),
@@ -140,6 +141,11 @@ def sw_set_workspace(ws):
 
 def sw_set_stream(stream_handle):
     return _check(lib().sw_set_stream(ctypes.c_void_p(stream_handle)))
+
+
+def sw_set_overlap(on):
+    """False/0: one stream; True/1: three streams, addition kernels capped at 256 workgroups; k > 1: cap k."""
+    return _check(lib().sw_set_overlap(int(on)))
 
 
 def sw_set_odd_mode(mode):

@@ -26,6 +26,21 @@ constexpr int ROWS = SW_ADD_ROWS;       // rows per thread (independent loads in
 constexpr int POST_ROWS = SW_ADD_POST_ROWS;
 constexpr int PAD_ROWS = 8;              // rows per thread of the pad / crop copy
 
+// Every kernel below walks a LOGICAL grid (column chunks x row groups x matrices) with however many
+// workgroups it was launched with: workgroup b takes logical blocks b, b + gridDim.x, ...  Launched with the
+// full grid this is the ordinary one-block-per-workgroup kernel; launched with a few hundred workgroups it is
+// a persistent streaming kernel that leaves most of every CU to the leaf products running beside it.
+struct LGrid { unsigned gx, gy, gz; };
+#define SW_LOGICAL_BLOCKS(lg)                                                                        \
+    for (unsigned long long w_ = blockIdx.x, n_ = (unsigned long long)(lg).gx * (lg).gy * (lg).gz; w_ < n_; \
+         w_ += gridDim.x)
+#define SW_DECODE_BLOCK(lg)                                       \
+    const unsigned bx = (unsigned)(w_ % (lg).gx);                 \
+    const unsigned long long t_ = w_ / (lg).gx;                   \
+    const unsigned by = (unsigned)(t_ % (lg).gy);                 \
+    const unsigned bz = (unsigned)(t_ / (lg).gy);                 \
+    (void)bz;
+
 template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef double type; };
 template <> struct VecT<2> { typedef double __attribute__((ext_vector_type(2))) type; };
@@ -58,69 +73,74 @@ __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 template <int SIDE, int VEC>
 __global__ void __launch_bounds__(NT)
 pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int h,
-               double* __restrict__ child, int64_t cld, int64_t cstride, int copies)
+               double* __restrict__ child, int64_t cld, int64_t cstride, int copies, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    if (cx >= h) return;
-    const int r0 = blockIdx.y * ROWS;
-    const double* P = parent + (int64_t)blockIdx.z * pstride;
-    double* O = child + (int64_t)blockIdx.z * (copies ? 7 : 4) * cstride;
-
-    V q11[ROWS], q12[ROWS], q21[ROWS], q22[ROWS];
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            const double* top = P + (int64_t)row * pld + cx;
-            const double* bot = P + (int64_t)(row + h) * pld + cx;
-            q11[r] = ld<VEC>(top);
-            q12[r] = ld<VEC>(top + h);
-            q21[r] = ld<VEC>(bot);
-            q22[r] = ld<VEC>(bot + h);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            double* o = O + (int64_t)row * cld + cx;
-            if (SIDE == 0) {
-                const V t2 = q21[r] + q22[r];
-                const V t3 = t2 - q11[r];
-                const V t4 = q11[r] - q21[r];
-                const V t5 = q12[r] - t3;
-                if (copies) {
-                    st<VEC>(o, q11[r]);
-                    st<VEC>(o + cstride, q12[r]);
-                    st<VEC>(o + 6 * cstride, q22[r]);
-                    o += 2 * cstride;
-                }
-                st<VEC>(o, t2);
-                st<VEC>(o + cstride, t3);
-                st<VEC>(o + 2 * cstride, t4);
-                st<VEC>(o + 3 * cstride, t5);
-            } else {
-                const V s2 = q12[r] - q11[r];
-                const V s3 = q22[r] - s2;
-                const V s4 = q22[r] - q12[r];
-                const V s6 = s3 - q21[r];
-                if (copies) {
-                    st<VEC>(o, q11[r]);
-                    st<VEC>(o + cstride, q21[r]);
-                    st<VEC>(o + 2 * cstride, s2);
-                    st<VEC>(o + 3 * cstride, s3);
-                    st<VEC>(o + 4 * cstride, s4);
-                    st<VEC>(o + 5 * cstride, q22[r]);
-                    st<VEC>(o + 6 * cstride, s6);
-                } else {
-                    st<VEC>(o, s2);
-                    st<VEC>(o + cstride, s3);
-                    st<VEC>(o + 2 * cstride, s4);
-                    st<VEC>(o + 3 * cstride, s6);
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            if (cx >= h) return;
+            const int r0 = by * ROWS;
+            const double* P = parent + (int64_t)bz * pstride;
+            double* O = child + (int64_t)bz * (copies ? 7 : 4) * cstride;
+    
+            V q11[ROWS], q12[ROWS], q21[ROWS], q22[ROWS];
+        #pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    const double* top = P + (int64_t)row * pld + cx;
+                    const double* bot = P + (int64_t)(row + h) * pld + cx;
+                    q11[r] = ld<VEC>(top);
+                    q12[r] = ld<VEC>(top + h);
+                    q21[r] = ld<VEC>(bot);
+                    q22[r] = ld<VEC>(bot + h);
                 }
             }
-        }
+        #pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    double* o = O + (int64_t)row * cld + cx;
+                    if (SIDE == 0) {
+                        const V t2 = q21[r] + q22[r];
+                        const V t3 = t2 - q11[r];
+                        const V t4 = q11[r] - q21[r];
+                        const V t5 = q12[r] - t3;
+                        if (copies) {
+                            st<VEC>(o, q11[r]);
+                            st<VEC>(o + cstride, q12[r]);
+                            st<VEC>(o + 6 * cstride, q22[r]);
+                            o += 2 * cstride;
+                        }
+                        st<VEC>(o, t2);
+                        st<VEC>(o + cstride, t3);
+                        st<VEC>(o + 2 * cstride, t4);
+                        st<VEC>(o + 3 * cstride, t5);
+                    } else {
+                        const V s2 = q12[r] - q11[r];
+                        const V s3 = q22[r] - s2;
+                        const V s4 = q22[r] - q12[r];
+                        const V s6 = s3 - q21[r];
+                        if (copies) {
+                            st<VEC>(o, q11[r]);
+                            st<VEC>(o + cstride, q21[r]);
+                            st<VEC>(o + 2 * cstride, s2);
+                            st<VEC>(o + 3 * cstride, s3);
+                            st<VEC>(o + 4 * cstride, s4);
+                            st<VEC>(o + 5 * cstride, q22[r]);
+                            st<VEC>(o + 6 * cstride, s6);
+                        } else {
+                            st<VEC>(o, s2);
+                            st<VEC>(o + cstride, s3);
+                            st<VEC>(o + 2 * cstride, s4);
+                            st<VEC>(o + 3 * cstride, s6);
+                        }
+                    }
+                }
+            }
+        }();
     }
 }
 
@@ -129,39 +149,44 @@ pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, 
 template <int VEC>
 __global__ void __launch_bounds__(NT)
 post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int h,
-                double* __restrict__ parent, int64_t pld, int64_t pstride)
+                double* __restrict__ parent, int64_t pld, int64_t pstride, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    constexpr int R = POST_ROWS;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    if (cx >= h) return;
-    const int r0 = blockIdx.y * R;
-    const double* q = Q + (int64_t)blockIdx.z * 7 * qstride;
-    double* P = parent + (int64_t)blockIdx.z * pstride;
-
-    V v[R][7];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-#pragma unroll
-            for (int j = 0; j < 7; ++j) v[r][j] = ld<VEC>(q + j * qstride + (int64_t)row * qld + cx);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            const V u1 = v[r][0] + v[r][3];
-            const V u2 = u1 + v[r][4];
-            const V u3 = u1 + v[r][2];
-            double* top = P + (int64_t)row * pld + cx;
-            double* bot = P + (int64_t)(row + h) * pld + cx;
-            st<VEC>(top, v[r][0] + v[r][1]);
-            st<VEC>(top + h, u3 + v[r][5]);
-            st<VEC>(bot, u2 - v[r][6]);
-            st<VEC>(bot + h, u2 + v[r][2]);
-        }
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            constexpr int R = POST_ROWS;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            if (cx >= h) return;
+            const int r0 = by * R;
+            const double* q = Q + (int64_t)bz * 7 * qstride;
+            double* P = parent + (int64_t)bz * pstride;
+    
+            V v[R][7];
+        #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+        #pragma unroll
+                    for (int j = 0; j < 7; ++j) v[r][j] = ld<VEC>(q + j * qstride + (int64_t)row * qld + cx);
+                }
+            }
+        #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    const V u1 = v[r][0] + v[r][3];
+                    const V u2 = u1 + v[r][4];
+                    const V u3 = u1 + v[r][2];
+                    double* top = P + (int64_t)row * pld + cx;
+                    double* bot = P + (int64_t)(row + h) * pld + cx;
+                    st<VEC>(top, v[r][0] + v[r][1]);
+                    st<VEC>(top + h, u3 + v[r][5]);
+                    st<VEC>(bot, u2 - v[r][6]);
+                    st<VEC>(bot + h, u2 + v[r][2]);
+                }
+            }
+        }();
     }
 }
 
@@ -180,32 +205,37 @@ struct EwOp {
 // exactly (same element, same thread), so no __restrict__ here.
 template <int VEC, int NOPS>
 __global__ void __launch_bounds__(NT)
-ew_kernel(EwOp op0, EwOp op1, int live, int h)
+ew_kernel(EwOp op0, EwOp op1, int live, int h, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    if (cx >= h) return;
-    const int r0 = blockIdx.y * ROWS;
-    int b = blockIdx.z;
-    const bool second = NOPS == 2 && b >= live;
-    if (second) b -= live;
-    const EwOp& op = second ? op1 : op0;
-    double* z = op.z + (int64_t)b * op.zstride;
-    const double* x = op.x + (int64_t)b * op.xstride;
-    const double* y = op.y + (int64_t)b * op.ystride;
-    V xv[ROWS], yv[ROWS];
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            xv[r] = ld<VEC>(x + (int64_t)row * op.xld + cx);
-            yv[r] = ld<VEC>(y + (int64_t)row * op.yld + cx);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const int row = r0 + r;
-        if (row < h) st<VEC>(z + (int64_t)row * op.zld + cx, op.sign > 0 ? xv[r] + yv[r] : xv[r] - yv[r]);
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            if (cx >= h) return;
+            const int r0 = by * ROWS;
+            int b = bz;
+            const bool second = NOPS == 2 && b >= live;
+            if (second) b -= live;
+            const EwOp& op = second ? op1 : op0;
+            double* z = op.z + (int64_t)b * op.zstride;
+            const double* x = op.x + (int64_t)b * op.xstride;
+            const double* y = op.y + (int64_t)b * op.ystride;
+            V xv[ROWS], yv[ROWS];
+        #pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    xv[r] = ld<VEC>(x + (int64_t)row * op.xld + cx);
+                    yv[r] = ld<VEC>(y + (int64_t)row * op.yld + cx);
+                }
+            }
+        #pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < h) st<VEC>(z + (int64_t)row * op.zld + cx, op.sign > 0 ? xv[r] + yv[r] : xv[r] - yv[r]);
+            }
+        }();
     }
 }
 
@@ -215,40 +245,45 @@ ew_kernel(EwOp op0, EwOp op1, int live, int h)
 template <int VEC>
 __global__ void __launch_bounds__(NT)
 dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11, double* c12, double* c21,
-                double* c22, int64_t cld, int64_t cstride, int h)
+                double* c22, int64_t cld, int64_t cstride, int h, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    constexpr int R = 2;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    if (cx >= h) return;
-    const int r0 = blockIdx.y * R;
-    const int64_t boff = (int64_t)blockIdx.z * cstride;
-    x += (int64_t)blockIdx.z * xstride;
-    V q0[R], q5[R], q3[R], q4[R], q2[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            const int64_t o = boff + (int64_t)row * cld + cx;
-            q0[r] = ld<VEC>(x + (int64_t)row * xld + cx);
-            q5[r] = ld<VEC>(c11 + o);
-            q3[r] = ld<VEC>(c12 + o);
-            q4[r] = ld<VEC>(c21 + o);
-            q2[r] = ld<VEC>(c22 + o);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int row = r0 + r;
-        if (row < h) {
-            const int64_t o = boff + (int64_t)row * cld + cx;
-            const V u1 = q0[r] + q3[r];
-            const V u2 = u1 + q4[r];
-            const V u3 = u1 + q2[r];
-            st<VEC>(c22 + o, u2 + q2[r]);
-            st<VEC>(c12 + o, u3 + q5[r]);
-            st<VEC>(c21 + o, u2);
-        }
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            constexpr int R = 2;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            if (cx >= h) return;
+            const int r0 = by * R;
+            const int64_t boff = (int64_t)bz * cstride;
+            const double* xb = x + (int64_t)bz * xstride;
+            V q0[R], q5[R], q3[R], q4[R], q2[R];
+        #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    const int64_t o = boff + (int64_t)row * cld + cx;
+                    q0[r] = ld<VEC>(xb + (int64_t)row * xld + cx);
+                    q5[r] = ld<VEC>(c11 + o);
+                    q3[r] = ld<VEC>(c12 + o);
+                    q4[r] = ld<VEC>(c21 + o);
+                    q2[r] = ld<VEC>(c22 + o);
+                }
+            }
+        #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = r0 + r;
+                if (row < h) {
+                    const int64_t o = boff + (int64_t)row * cld + cx;
+                    const V u1 = q0[r] + q3[r];
+                    const V u2 = u1 + q4[r];
+                    const V u3 = u1 + q2[r];
+                    st<VEC>(c22 + o, u2 + q2[r]);
+                    st<VEC>(c12 + o, u3 + q5[r]);
+                    st<VEC>(c21 + o, u2);
+                }
+            }
+        }();
     }
 }
 
@@ -276,32 +311,37 @@ __device__ __forceinline__ void winograd_pre(const V x11, const V x12, const V x
 template <int SIDE, int VEC>
 __global__ void __launch_bounds__(NT)
 pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int m,
-                double* __restrict__ child, int64_t cld, int64_t cstride)
+                double* __restrict__ child, int64_t cld, int64_t cstride, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    const int row = blockIdx.y;
-    if (cx >= m) return;
-    const double* P = parent + (int64_t)blockIdx.z * pstride + (int64_t)row * pld + cx;
-    double* O = child + (int64_t)blockIdx.z * 49 * cstride + (int64_t)row * cld + cx;
-
-    V a[4][4];
-#pragma unroll
-    for (int R = 0; R < 4; ++R)
-#pragma unroll
-        for (int C = 0; C < 4; ++C) a[R][C] = ld<VEC>(P + (int64_t)R * m * pld + C * m);
-
-    V t[4][7];   // t[2p+q][j] = T_j[p][q]
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int q = 0; q < 2; ++q) winograd_pre<SIDE, V>(a[p][q], a[p][2 + q], a[2 + p][q], a[2 + p][2 + q], t[2 * p + q]);
-#pragma unroll
-    for (int j = 0; j < 7; ++j) {
-        V o[7];
-        winograd_pre<SIDE, V>(t[0][j], t[1][j], t[2][j], t[3][j], o);
-#pragma unroll
-        for (int i = 0; i < 7; ++i) st<VEC>(O + (int64_t)(j * 7 + i) * cstride, o[i]);
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            const int row = by;
+            if (cx >= m) return;
+            const double* P = parent + (int64_t)bz * pstride + (int64_t)row * pld + cx;
+            double* O = child + (int64_t)bz * 49 * cstride + (int64_t)row * cld + cx;
+    
+            V a[4][4];
+        #pragma unroll
+            for (int R = 0; R < 4; ++R)
+        #pragma unroll
+                for (int C = 0; C < 4; ++C) a[R][C] = ld<VEC>(P + (int64_t)R * m * pld + C * m);
+    
+            V t[4][7];   // t[2p+q][j] = T_j[p][q]
+        #pragma unroll
+            for (int p = 0; p < 2; ++p)
+        #pragma unroll
+                for (int q = 0; q < 2; ++q) winograd_pre<SIDE, V>(a[p][q], a[p][2 + q], a[2 + p][q], a[2 + p][2 + q], t[2 * p + q]);
+        #pragma unroll
+            for (int j = 0; j < 7; ++j) {
+                V o[7];
+                winograd_pre<SIDE, V>(t[0][j], t[1][j], t[2][j], t[3][j], o);
+        #pragma unroll
+                for (int i = 0; i < 7; ++i) st<VEC>(O + (int64_t)(j * 7 + i) * cstride, o[i]);
+            }
+        }();
     }
 }
 
@@ -310,76 +350,86 @@ pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride,
 template <int VEC>
 __global__ void __launch_bounds__(NT)
 post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int m,
-                 double* __restrict__ parent, int64_t pld, int64_t pstride)
+                 double* __restrict__ parent, int64_t pld, int64_t pstride, LGrid lg)
 {
-    typedef typename VecT<VEC>::type V;
-    const int cx = (blockIdx.x * NT + threadIdx.x) * VEC;
-    const int row = blockIdx.y;
-    if (cx >= m) return;
-    const double* q = Q + (int64_t)blockIdx.z * 49 * qstride + (int64_t)row * qld + cx;
-    double* P = parent + (int64_t)blockIdx.z * pstride + (int64_t)row * pld + cx;
-
-    // Q_j as four blocks [11, 12, 21, 22] from the seven products of child j
-    auto child = [&](int j, V (&out)[4]) __attribute__((always_inline)) {
-        V v[7];
-#pragma unroll
-        for (int i = 0; i < 7; ++i) v[i] = ld<VEC>(q + (int64_t)(j * 7 + i) * qstride);
-        const V u1 = v[0] + v[3];
-        const V u2 = u1 + v[4];
-        const V u3 = u1 + v[2];
-        out[0] = v[0] + v[1];
-        out[1] = u3 + v[5];
-        out[2] = u2 - v[6];
-        out[3] = u2 + v[2];
-    };
-    // store the four blocks of the parent's quadrant (X, Y)
-    auto put = [&](int X, int Y, const V (&c)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int pq = 0; pq < 4; ++pq)
-            st<VEC>(P + (int64_t)(2 * X + (pq >> 1)) * m * pld + (2 * Y + (pq & 1)) * m, c[pq]);
-    };
-
-    V q0[4], q3[4], u1[4], u2[4], u3[4], t[4], c[4];
-    child(0, q0);
-    child(3, q3);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) u1[k] = q0[k] + q3[k];          // U1 = Q0 + Q3
-    child(1, t);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) c[k] = q0[k] + t[k];            // C11 = Q0 + Q1
-    put(0, 0, c);
-    child(4, t);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) u2[k] = u1[k] + t[k];           // U2 = U1 + Q4
-    child(2, t);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { u3[k] = u1[k] + t[k]; c[k] = u2[k] + t[k]; }   // U3 = U1 + Q2, C22 = U2 + Q2
-    put(1, 1, c);
-    child(5, t);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) c[k] = u3[k] + t[k];            // C12 = U3 + Q5
-    put(0, 1, c);
-    child(6, t);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) c[k] = u2[k] - t[k];            // C21 = U2 - Q6
-    put(1, 0, c);
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            typedef typename VecT<VEC>::type V;
+            const int cx = (bx * NT + threadIdx.x) * VEC;
+            const int row = by;
+            if (cx >= m) return;
+            const double* q = Q + (int64_t)bz * 49 * qstride + (int64_t)row * qld + cx;
+            double* P = parent + (int64_t)bz * pstride + (int64_t)row * pld + cx;
+    
+            // Q_j as four blocks [11, 12, 21, 22] from the seven products of child j
+            auto child = [&](int j, V (&out)[4]) __attribute__((always_inline)) {
+                V v[7];
+        #pragma unroll
+                for (int i = 0; i < 7; ++i) v[i] = ld<VEC>(q + (int64_t)(j * 7 + i) * qstride);
+                const V u1 = v[0] + v[3];
+                const V u2 = u1 + v[4];
+                const V u3 = u1 + v[2];
+                out[0] = v[0] + v[1];
+                out[1] = u3 + v[5];
+                out[2] = u2 - v[6];
+                out[3] = u2 + v[2];
+            };
+            // store the four blocks of the parent's quadrant (X, Y)
+            auto put = [&](int X, int Y, const V (&c)[4]) __attribute__((always_inline)) {
+        #pragma unroll
+                for (int pq = 0; pq < 4; ++pq)
+                    st<VEC>(P + (int64_t)(2 * X + (pq >> 1)) * m * pld + (2 * Y + (pq & 1)) * m, c[pq]);
+            };
+    
+            V q0[4], q3[4], u1[4], u2[4], u3[4], t[4], c[4];
+            child(0, q0);
+            child(3, q3);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) u1[k] = q0[k] + q3[k];          // U1 = Q0 + Q3
+            child(1, t);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) c[k] = q0[k] + t[k];            // C11 = Q0 + Q1
+            put(0, 0, c);
+            child(4, t);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) u2[k] = u1[k] + t[k];           // U2 = U1 + Q4
+            child(2, t);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) { u3[k] = u1[k] + t[k]; c[k] = u2[k] + t[k]; }   // U3 = U1 + Q2, C22 = U2 + Q2
+            put(1, 1, c);
+            child(5, t);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) c[k] = u3[k] + t[k];            // C12 = U3 + Q5
+            put(0, 1, c);
+            child(6, t);
+        #pragma unroll
+            for (int k = 0; k < 4; ++k) c[k] = u2[k] - t[k];            // C21 = U2 - Q6
+            put(1, 0, c);
+        }();
+    }
 }
 
 // ---- zero-padded copy ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT)
 pad_copy_kernel(const double* __restrict__ src, int64_t sld, int rows, int cols, double* __restrict__ dst,
-                int64_t dld, int prows, int pcols)
+                int64_t dld, int prows, int pcols, LGrid lg)
 {
-    const int c = blockIdx.x * NT + threadIdx.x;
-    if (c >= pcols) return;
-    const int r0 = blockIdx.y * PAD_ROWS;
-#pragma unroll
-    for (int r = 0; r < PAD_ROWS; ++r) {
-        const int row = r0 + r;
-        if (row < prows) {
-            const double v = (row < rows && c < cols) ? src[(int64_t)row * sld + c] : 0.0;
-            dst[(int64_t)row * dld + c] = v;
-        }
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            const int c = bx * NT + threadIdx.x;
+            if (c >= pcols) return;
+            const int r0 = by * PAD_ROWS;
+        #pragma unroll
+            for (int r = 0; r < PAD_ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < prows) {
+                    const double v = (row < rows && c < cols) ? src[(int64_t)row * sld + c] : 0.0;
+                    dst[(int64_t)row * dld + c] = v;
+                }
+            }
+        }();
     }
 }
 
@@ -387,22 +437,33 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool even(int64_t v) { return (v & 1) == 0; }
 inline bool mat_vec2(const Mat& m) { return aligned16(m.p) && even(m.ld) && even(m.stride); }
 
-inline dim3 grid_for(int64_t h, int vec, int rows, int64_t batch)
+inline LGrid grid_for(int64_t h, int vec, int rows, int64_t batch)
 {
     const int64_t chunks = (h + vec - 1) / vec;
-    return dim3((unsigned)((chunks + NT - 1) / NT), (unsigned)((h + rows - 1) / rows), (unsigned)batch);
+    return LGrid{(unsigned)((chunks + NT - 1) / NT), (unsigned)((h + rows - 1) / rows), (unsigned)batch};
+}
+
+static int g_block_cap = 0;   // 0: one workgroup per logical block; else at most this many workgroups per launch
+
+inline dim3 physical(const LGrid& lg)
+{
+    const unsigned long long total = (unsigned long long)lg.gx * lg.gy * lg.gz;
+    const unsigned long long cap = g_block_cap > 0 ? (unsigned long long)g_block_cap : 0x7fffffffULL;
+    return dim3((unsigned)(total < cap ? total : cap));
 }
 
 }  // namespace
+
+void set_add_block_cap(int cap) { g_block_cap = cap; }
 
 hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s)
 {
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(child);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, live);
+    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                              \
-    hipLaunchKernelGGL((pre_add_kernel<SIDE, VEC>), g, dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
-                       (int)h, child.p, child.ld, child.stride, copies ? 1 : 0)
+    hipLaunchKernelGGL((pre_add_kernel<SIDE, VEC>), physical(lg), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
+                       (int)h, child.p, child.ld, child.stride, copies ? 1 : 0, lg)
     if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
     else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
 #undef SW_LAUNCH
@@ -413,13 +474,13 @@ hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream
 {
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(q);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, POST_ROWS, live);
+    const LGrid lg = grid_for(h, v2 ? 2 : 1, POST_ROWS, live);
     if (v2)
-        hipLaunchKernelGGL((post_add_kernel<2>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
-                           parent.ld, parent.stride);
+        hipLaunchKernelGGL((post_add_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+                           parent.ld, parent.stride, lg);
     else
-        hipLaunchKernelGGL((post_add_kernel<1>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
-                           parent.ld, parent.stride);
+        hipLaunchKernelGGL((post_add_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+                           parent.ld, parent.stride, lg);
     return hipGetLastError();
 }
 
@@ -427,10 +488,10 @@ hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat ch
 {
     if (live == 0 || m == 0) return hipSuccess;
     const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(child);
-    const dim3 g = grid_for(m, v2 ? 2 : 1, 1, live);
+    const LGrid lg = grid_for(m, v2 ? 2 : 1, 1, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                               \
-    hipLaunchKernelGGL((pre_add2_kernel<SIDE, VEC>), g, dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
-                       (int)m, child.p, child.ld, child.stride)
+    hipLaunchKernelGGL((pre_add2_kernel<SIDE, VEC>), physical(lg), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
+                       (int)m, child.p, child.ld, child.stride, lg)
     if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
     else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
 #undef SW_LAUNCH
@@ -441,13 +502,13 @@ hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStrea
 {
     if (live == 0 || m == 0) return hipSuccess;
     const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(q);
-    const dim3 g = grid_for(m, v2 ? 2 : 1, 1, live);
+    const LGrid lg = grid_for(m, v2 ? 2 : 1, 1, live);
     if (v2)
-        hipLaunchKernelGGL((post_add2_kernel<2>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
-                           parent.ld, parent.stride);
+        hipLaunchKernelGGL((post_add2_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
+                           parent.ld, parent.stride, lg);
     else
-        hipLaunchKernelGGL((post_add2_kernel<1>), g, dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
-                           parent.ld, parent.stride);
+        hipLaunchKernelGGL((post_add2_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
+                           parent.ld, parent.stride, lg);
     return hipGetLastError();
 }
 
@@ -460,10 +521,10 @@ hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hip
 {
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(z) && mat_vec2(x) && mat_vec2(y);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, live);
+    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, live);
     const EwOp op = make_op(z, x, y, sign);
-    if (v2) hipLaunchKernelGGL((ew_kernel<2, 1>), g, dim3(NT), 0, s, op, op, (int)live, (int)h);
-    else    hipLaunchKernelGGL((ew_kernel<1, 1>), g, dim3(NT), 0, s, op, op, (int)live, (int)h);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)h, lg);
+    else    hipLaunchKernelGGL((ew_kernel<1, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)h, lg);
     return hipGetLastError();
 }
 
@@ -473,10 +534,10 @@ hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1,
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = even(h) && mat_vec2(z0) && mat_vec2(x0) && mat_vec2(y0) && mat_vec2(z1) && mat_vec2(x1) &&
                     mat_vec2(y1);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, ROWS, 2 * live);
+    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, 2 * live);
     const EwOp a = make_op(z0, x0, y0, sign0), b = make_op(z1, x1, y1, sign1);
-    if (v2) hipLaunchKernelGGL((ew_kernel<2, 2>), g, dim3(NT), 0, s, a, b, (int)live, (int)h);
-    else    hipLaunchKernelGGL((ew_kernel<1, 2>), g, dim3(NT), 0, s, a, b, (int)live, (int)h);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)h, lg);
+    else    hipLaunchKernelGGL((ew_kernel<1, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)h, lg);
     return hipGetLastError();
 }
 
@@ -485,13 +546,13 @@ hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t li
     if (live == 0 || h == 0) return hipSuccess;
     // the four quadrants share ld and stride by construction
     const bool v2 = even(h) && mat_vec2(x) && mat_vec2(c11) && mat_vec2(c12) && mat_vec2(c21) && mat_vec2(c22);
-    const dim3 g = grid_for(h, v2 ? 2 : 1, 2, live);
+    const LGrid lg = grid_for(h, v2 ? 2 : 1, 2, live);
     if (v2)
-        hipLaunchKernelGGL((dfs_post_kernel<2>), g, dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
-                           c22.p, c11.ld, c11.stride, (int)h);
+        hipLaunchKernelGGL((dfs_post_kernel<2>), physical(lg), dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
+                           c22.p, c11.ld, c11.stride, (int)h, lg);
     else
-        hipLaunchKernelGGL((dfs_post_kernel<1>), g, dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
-                           c22.p, c11.ld, c11.stride, (int)h);
+        hipLaunchKernelGGL((dfs_post_kernel<1>), physical(lg), dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
+                           c22.p, c11.ld, c11.stride, (int)h, lg);
     return hipGetLastError();
 }
 
@@ -499,9 +560,9 @@ hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int6
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s)
 {
     if (prows == 0 || pcols == 0) return hipSuccess;
-    const dim3 g((unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + PAD_ROWS - 1) / PAD_ROWS), 1);
-    hipLaunchKernelGGL(pad_copy_kernel, g, dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
-                       (int)prows, (int)pcols);
+    const LGrid lg{(unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + PAD_ROWS - 1) / PAD_ROWS), 1u};
+    hipLaunchKernelGGL(pad_copy_kernel, physical(lg), dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
+                       (int)prows, (int)pcols, lg);
     return hipGetLastError();
 }
 

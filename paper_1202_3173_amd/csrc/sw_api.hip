@@ -36,6 +36,8 @@ static void* g_ws = nullptr;
 static int64_t g_ws_bytes = 0;
 static hipStream_t g_stream = nullptr;
 static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divide n
+static int g_overlap = 256;           // > 0: additions and leaf products on separate streams, the addition
+                                      // kernels then run with at most this many workgroups; 0: one stream
 
 // ---- profiling ------------------------------------------------------------------------------------------------
 
@@ -142,16 +144,154 @@ static int plan(int64_t n, int levels, int64_t budget, char* out)
     return SW_OK;
 }
 
+// ---- three in-order streams with tracked dependencies ----------------------------------------------------------
+//
+// The additions are bound by HBM and the leaf products by the matrix cores, so they are run side by side:
+// kernels that FORM operands (pre-additions) go to one stream, leaf products to a second, kernels that FOLD
+// products into C (post-additions) stay on the caller's stream.  Every kernel declares the address ranges it
+// reads and writes; before a launch the stream is made to wait (hipStreamWaitEvent) for every earlier kernel of
+// ANOTHER stream that conflicts with it (read-after-write, write-after-read, write-after-write).  Order inside
+// a stream needs nothing.  Correctness therefore never rests on how the executor happens to interleave its
+// calls: a buffer used too early is a declared conflict and becomes a wait.  All waits point to kernels
+// submitted earlier, so they cannot form a cycle.
+
+enum { S_POST = 0, S_PRE = 1, S_MM = 2, NSTREAM = 3 };
+
+struct Range { uintptr_t lo, hi; };
+
+// bounding byte range of `count` matrices of rows x cols
+static Range rng(const Mat& m, int64_t rows, int64_t cols, int64_t count = 1)
+{
+    const uintptr_t lo = (uintptr_t)m.p;
+    return Range{lo, lo + (uintptr_t)(((count - 1) * m.stride + (rows - 1) * m.ld + cols) * (int64_t)sizeof(double))};
+}
+
+struct Sched {
+    static constexpr int RING = 256;
+    hipStream_t st[NSTREAM] = {nullptr, nullptr, nullptr};
+    bool multi = false;
+    uint64_t seq[NSTREAM] = {0, 0, 0};              // kernels issued per stream
+    uint64_t waited[NSTREAM][NSTREAM] = {};         // waited[c][s]: stream c is ordered after kernel number .. of s
+    struct Acc { uintptr_t lo, hi; uint64_t seq; uint8_t stream; bool write; };
+    std::vector<Acc> live;
+    hipError_t err = hipSuccess;
+
+    // process-wide pool: two internal streams and the event rings (created once, never destroyed)
+    struct Pool { hipStream_t pre = nullptr, mm = nullptr; hipEvent_t ring[NSTREAM][RING]; hipEvent_t entry; bool ok = false; };
+    static Pool& pool()
+    {
+        static Pool p;
+        if (!p.ok) {
+            bool good = hipStreamCreateWithFlags(&p.pre, hipStreamNonBlocking) == hipSuccess &&
+                        hipStreamCreateWithFlags(&p.mm, hipStreamNonBlocking) == hipSuccess &&
+                        hipEventCreateWithFlags(&p.entry, hipEventDisableTiming) == hipSuccess;
+            for (int s = 0; s < NSTREAM && good; ++s)
+                for (int i = 0; i < RING && good; ++i)
+                    good = hipEventCreateWithFlags(&p.ring[s][i], hipEventDisableTiming) == hipSuccess;
+            p.ok = good;
+        }
+        return p;
+    }
+
+    void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+
+    // the caller's stream carries the post-additions; the two others first wait for what the caller queued
+    void start(hipStream_t caller, bool want_multi)
+    {
+        st[S_POST] = st[S_PRE] = st[S_MM] = caller;
+        multi = false;
+        if (!want_multi) return;
+        // under stream capture everything stays on the capturing stream: the graph then holds the kernels in
+        // program order (forking a capture over the library's own streams is not attempted)
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(caller, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+        if (cap != hipStreamCaptureStatusNone) return;
+        Pool& p = pool();
+        if (!p.ok) return;                          // no streams or events to be had: stay on one stream
+        multi = true;
+        st[S_PRE] = p.pre;
+        st[S_MM] = p.mm;
+        note(hipEventRecord(p.entry, caller));
+        note(hipStreamWaitEvent(p.pre, p.entry, 0));
+        note(hipStreamWaitEvent(p.mm, p.entry, 0));
+    }
+
+    void wait_for(int c, int s, uint64_t n)          // stream c waits for kernel number n (1-based) of stream s
+    {
+        if (c == s || waited[c][s] >= n) return;
+        const uint64_t use = (seq[s] - n < (uint64_t)RING) ? n : seq[s];   // its own event, or a later one
+        note(hipStreamWaitEvent(st[c], pool().ring[s][(use - 1) % RING], 0));
+        waited[c][s] = use;
+    }
+
+    static bool hit(const Range& r, const Acc& a) { return r.lo < a.hi && a.lo < r.hi; }
+
+    void acquire(int c, const Range* reads, int nr, const Range* writes, int nw)
+    {
+        if (!multi) return;
+        for (const Acc& a : live) {
+            if (a.stream == c || waited[c][a.stream] >= a.seq) continue;
+            bool conflict = false;
+            for (int i = 0; i < nw && !conflict; ++i) conflict = hit(writes[i], a);
+            if (a.write)
+                for (int i = 0; i < nr && !conflict; ++i) conflict = hit(reads[i], a);
+            if (conflict) wait_for(c, a.stream, a.seq);
+        }
+    }
+
+    void release(int c, const Range* reads, int nr, const Range* writes, int nw)
+    {
+        if (!multi) return;
+        ++seq[c];
+        note(hipEventRecord(pool().ring[c][(seq[c] - 1) % RING], st[c]));
+        for (int i = 0; i < nr; ++i) live.push_back(Acc{reads[i].lo, reads[i].hi, seq[c], (uint8_t)c, false});
+        for (int i = 0; i < nw; ++i) live.push_back(Acc{writes[i].lo, writes[i].hi, seq[c], (uint8_t)c, true});
+        if (live.size() >= 512) prune();
+    }
+
+    void join_all()
+    {
+        for (int c = 0; c < NSTREAM; ++c)
+            for (int s = 0; s < NSTREAM; ++s)
+                if (seq[s] > 0) wait_for(c, s, seq[s]);
+    }
+
+    void prune()
+    {
+        // forget what every other stream is already ordered after; if that does not help, order everything
+        auto settled = [&](const Acc& a) {
+            for (int c = 0; c < NSTREAM; ++c)
+                if (c != a.stream && waited[c][a.stream] < a.seq) return false;
+            return true;
+        };
+        size_t k = 0;
+        for (size_t i = 0; i < live.size(); ++i)
+            if (!settled(live[i])) live[k++] = live[i];
+        live.resize(k);
+        if (live.size() >= 384) { join_all(); live.clear(); }
+    }
+
+    // the caller's stream ends up ordered after everything
+    void finish()
+    {
+        if (!multi) return;
+        for (int s = 1; s < NSTREAM; ++s)
+            if (seq[s] > 0) wait_for(S_POST, s, seq[s]);
+    }
+};
+
 // ---- the executor ----------------------------------------------------------------------------------------------
 
 struct Exec {
-    hipStream_t stream;
+    Sched sc;
     char* ws;
     int64_t ws_bytes;
     int64_t used = 0;
     const char* sched;
     int levels;
-    uint32_t rich = 0;      // DFS levels that keep BFS-style storage (choose_rich)
+    uint32_t rich = 0;      // DFS levels that keep BFS-style storage (choose_options)
+    bool dbl = false;       // the buffers next to the leaves exist twice and alternate between launches
+    uint64_t flip = 0;
     Profiler* prof;
     hipError_t err = hipSuccess;
 
@@ -167,18 +307,32 @@ struct Exec {
     // bytes moved by an element-wise kernel with `nin` input and `nout` output matrices of h x h
     static double bytes(int64_t live, int64_t h, int nin, int nout) { return 8.0 * live * h * h * (nin + nout); }
 
-    void ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h)
+    // One kernel: on stream `s`, after everything of the other streams it conflicts with.
+    template <class F>
+    void op(int s, int cls, double work, std::initializer_list<Range> reads, std::initializer_list<Range> writes, F&& launch)
     {
-        prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 2, 1));
-        note(launch_ew(z, x, y, sign, live, h, stream));
-        prof_end(prof, stream);
+        if (err != hipSuccess) return;
+        sc.acquire(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
+        prof_begin(prof, sc.st[s], cls, work);
+        note(launch(sc.st[s]));
+        prof_end(prof, sc.st[s]);
+        sc.release(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
+        note(sc.err);
     }
 
-    void ew2(Mat z0, Mat x0, Mat y0, int s0, Mat z1, Mat x1, Mat y1, int s1, int64_t live, int64_t h)
+    // Z = X + sign * Y (stream s: S_PRE when Z is an operand of a product, S_POST when it is part of C)
+    void ew(int s, Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h)
     {
-        prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 4, 2));
-        note(launch_ew2(z0, x0, y0, s0, z1, x1, y1, s1, live, h, stream));
-        prof_end(prof, stream);
+        op(s, SW_CLASS_DFS_ADD, bytes(live, h, 2, 1), {rng(x, h, h, live), rng(y, h, h, live)}, {rng(z, h, h, live)},
+           [&](hipStream_t st) { return launch_ew(z, x, y, sign, live, h, st); });
+    }
+
+    void ew2(int s, Mat z0, Mat x0, Mat y0, int s0, Mat z1, Mat x1, Mat y1, int s1, int64_t live, int64_t h)
+    {
+        op(s, SW_CLASS_DFS_ADD, bytes(live, h, 4, 2),
+           {rng(x0, h, h, live), rng(y0, h, h, live), rng(x1, h, h, live), rng(y1, h, h, live)},
+           {rng(z0, h, h, live), rng(z1, h, h, live)},
+           [&](hipStream_t st) { return launch_ew2(z0, x0, y0, s0, z1, x1, y1, s1, live, h, st); });
     }
 
     // C = A * B for `live` independent n x n problems, steps sched[level..] (Algorithm 2: procedures DFS and BFS).
@@ -186,63 +340,58 @@ struct Exec {
     {
         if (err != hipSuccess) return;
         if (level == levels) {
-            prof_begin(prof, stream, SW_CLASS_LEAF, 2.0 * live * (double)n * (double)n * (double)n);
-            note(launch_leaf_gemm(n, live, A, B, C, stream));
-            prof_end(prof, stream);
+            op(S_MM, SW_CLASS_LEAF, 2.0 * live * (double)n * (double)n * (double)n,
+               {rng(A, n, n, live), rng(B, n, n, live)}, {rng(C, n, n, live)},
+               [&](hipStream_t st) { return launch_leaf_gemm(n, live, A, B, C, st); });
             return;
         }
         const int64_t h = n / 2;
         const int64_t e = ws_mat_elems(h);
         const int64_t mark = used;
-        if (fuse_two_bfs(sched + level)) {
+        const bool fused = fuse_two_bfs(sched + level);
+        // the step whose children are the leaves: with two sets of buffers, consecutive launches alternate
+        if (dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels && (flip++ & 1))
+            used += (fused ? 3 * 49 * live * ws_mat_elems(h / 2) : 21 * live * e) * (int64_t)sizeof(double);
+        if (fused) {
             // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
             // their products go straight back; the level in between exists in registers only
             const int64_t m = h / 2;
             const int64_t e4 = ws_mat_elems(m);
             Mat T = ws_mat(take(49 * live * e4), m), S = ws_mat(take(49 * live * e4), m), Q = ws_mat(take(49 * live * e4), m);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49));
-            note(launch_pre_add2(0, A, live, m, T, stream));
-            prof_end(prof, stream);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49));
-            note(launch_pre_add2(1, B, live, m, S, stream));
-            prof_end(prof, stream);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49), {rng(A, n, n, live)}, {rng(T, m, m, 49 * live)},
+               [&](hipStream_t st) { return launch_pre_add2(0, A, live, m, T, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49), {rng(B, n, n, live)}, {rng(S, m, m, 49 * live)},
+               [&](hipStream_t st) { return launch_pre_add2(1, B, live, m, S, st); });
             mul(T, S, Q, m, level + 2, 49 * live);
-            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, m, 49, 16));
-            note(launch_post_add2(Q, live, m, C, stream));
-            prof_end(prof, stream);
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, m, 49, 16), {rng(Q, m, m, 49 * live)}, {rng(C, n, n, live)},
+               [&](hipStream_t st) { return launch_post_add2(Q, live, m, C, st); });
         } else if (sched[level] == 'B') {
             // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
             Mat T = ws_mat(take(7 * live * e), h), S = ws_mat(take(7 * live * e), h), Q = ws_mat(take(7 * live * e), h);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
-            note(launch_pre_add(0, A, live, h, T, true, stream));
-            prof_end(prof, stream);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7));
-            note(launch_pre_add(1, B, live, h, S, true, stream));
-            prof_end(prof, stream);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7), {rng(A, n, n, live)}, {rng(T, h, h, 7 * live)},
+               [&](hipStream_t st) { return launch_pre_add(0, A, live, h, T, true, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7), {rng(B, n, n, live)}, {rng(S, h, h, 7 * live)},
+               [&](hipStream_t st) { return launch_pre_add(1, B, live, h, S, true, st); });
             mul(T, S, Q, h, level + 1, 7 * live);
-            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, h, 7, 4));
-            note(launch_post_add(Q, live, h, C, stream));
-            prof_end(prof, stream);
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h, 7, 4), {rng(Q, h, h, 7 * live)}, {rng(C, n, n, live)},
+               [&](hipStream_t st) { return launch_post_add(Q, live, h, C, st); });
         } else if (rich & (1u << level)) {
             // DFS step with the storage of a BFS step: the four non-trivial T, four S and seven Q of every
             // parent are kept, so the additions are the one-pass BFS kernels (27 instead of 38 half-size
             // matrices moved per parent), but the seven subproblems are still solved in sequence.
             Mat Tn = ws_mat(take(4 * live * e), h), Sn = ws_mat(take(4 * live * e), h), Q = ws_mat(take(7 * live * e), h);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4));
-            note(launch_pre_add(0, A, live, h, Tn, false, stream));
-            prof_end(prof, stream);
-            prof_begin(prof, stream, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4));
-            note(launch_pre_add(1, B, live, h, Sn, false, stream));
-            prof_end(prof, stream);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4), {rng(A, n, n, live)}, {rng(Tn, h, h, 4 * live)},
+               [&](hipStream_t st) { return launch_pre_add(0, A, live, h, Tn, false, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4), {rng(B, n, n, live)}, {rng(Sn, h, h, 4 * live)},
+               [&](hipStream_t st) { return launch_pre_add(1, B, live, h, Sn, false, st); });
             auto slot = [&](const Mat& base, int k, int per) { return Mat{base.p + k * e, base.ld, per * e, base.padded}; };
             const Mat Ta[7] = {quad(A, h, 0, 0), quad(A, h, 0, 1), slot(Tn, 0, 4), slot(Tn, 1, 4), slot(Tn, 2, 4),
                                slot(Tn, 3, 4), quad(A, h, 1, 1)};
             const Mat Sb[7] = {quad(B, h, 0, 0), quad(B, h, 1, 0), slot(Sn, 0, 4), slot(Sn, 1, 4), slot(Sn, 2, 4),
                                quad(B, h, 1, 1), slot(Sn, 3, 4)};
             for (int j = 0; j < 7; ++j) mul(Ta[j], Sb[j], slot(Q, j, 7), h, level + 1, live);
-            prof_begin(prof, stream, SW_CLASS_POST_ADD, bytes(live, h, 7, 4));
-            note(launch_post_add(Q, live, h, C, stream));
-            prof_end(prof, stream);
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h, 7, 4), {rng(Q, h, h, 7 * live)}, {rng(C, n, n, live)},
+               [&](hipStream_t st) { return launch_post_add(Q, live, h, C, st); });
         } else {
             // DFS step: the seven products one after the other (Section 3.4), written straight into the
             // quadrants of C, with two temporaries X, Y per parent.  The additions are those of Appendix A
@@ -251,23 +400,24 @@ struct Exec {
             const Mat A11 = quad(A, h, 0, 0), A12 = quad(A, h, 0, 1), A21 = quad(A, h, 1, 0), A22 = quad(A, h, 1, 1);
             const Mat B11 = quad(B, h, 0, 0), B12 = quad(B, h, 0, 1), B21 = quad(B, h, 1, 0), B22 = quad(B, h, 1, 1);
             const Mat C11 = quad(C, h, 0, 0), C12 = quad(C, h, 0, 1), C21 = quad(C, h, 1, 0), C22 = quad(C, h, 1, 1);
-            ew2(X, A11, A21, -1, Y, B22, B12, -1, live, h);     // T4 = A11 - A21, S4 = B22 - B12
-            mul(X, Y, C21, h, level + 1, live);                 // C21 <- Q4
-            ew2(X, A21, A22, +1, Y, B12, B11, -1, live, h);     // T2 = A21 + A22, S2 = B12 - B11
-            mul(X, Y, C22, h, level + 1, live);                 // C22 <- Q2
-            ew2(X, X, A11, -1, Y, B22, Y, -1, live, h);         // T3 = T2 - A11,  S3 = B22 - S2
-            mul(X, Y, C12, h, level + 1, live);                 // C12 <- Q3
-            ew(X, A12, X, -1, live, h);                         // T5 = A12 - T3
-            mul(X, B22, C11, h, level + 1, live);               // C11 <- Q5 = T5 * B22
-            mul(A11, B11, X, h, level + 1, live);               // X   <- Q0 = A11 * B11
-            prof_begin(prof, stream, SW_CLASS_DFS_ADD, bytes(live, h, 5, 3));
-            note(launch_dfs_post(X, C11, C12, C21, C22, live, h, stream));  // C12, C22 final; C21 = U2
-            prof_end(prof, stream);
-            ew(Y, Y, B21, -1, live, h);                         // S6 = S3 - B21
-            mul(A22, Y, C11, h, level + 1, live);               // C11 <- Q6 = A22 * S6
-            ew(C21, C21, C11, -1, live, h);                     // C21 = U2 - Q6
-            mul(A12, B21, C11, h, level + 1, live);             // C11 <- Q1 = A12 * B21
-            ew(C11, X, C11, +1, live, h);                       // C11 = Q0 + Q1
+            ew2(S_PRE, X, A11, A21, -1, Y, B22, B12, -1, live, h);     // T4 = A11 - A21, S4 = B22 - B12
+            mul(X, Y, C21, h, level + 1, live);                        // C21 <- Q4
+            ew2(S_PRE, X, A21, A22, +1, Y, B12, B11, -1, live, h);     // T2 = A21 + A22, S2 = B12 - B11
+            mul(X, Y, C22, h, level + 1, live);                        // C22 <- Q2
+            ew2(S_PRE, X, X, A11, -1, Y, B22, Y, -1, live, h);         // T3 = T2 - A11,  S3 = B22 - S2
+            mul(X, Y, C12, h, level + 1, live);                        // C12 <- Q3
+            ew(S_PRE, X, A12, X, -1, live, h);                         // T5 = A12 - T3
+            mul(X, B22, C11, h, level + 1, live);                      // C11 <- Q5 = T5 * B22
+            mul(A11, B11, X, h, level + 1, live);                      // X   <- Q0 = A11 * B11
+            op(S_POST, SW_CLASS_DFS_ADD, bytes(live, h, 5, 3),
+               {rng(X, h, h, live), rng(C11, h, h, live), rng(C12, h, h, live), rng(C21, h, h, live), rng(C22, h, h, live)},
+               {rng(C12, h, h, live), rng(C21, h, h, live), rng(C22, h, h, live)},
+               [&](hipStream_t st) { return launch_dfs_post(X, C11, C12, C21, C22, live, h, st); });  // C12, C22 final; C21 = U2
+            ew(S_PRE, Y, Y, B21, -1, live, h);                         // S6 = S3 - B21
+            mul(A22, Y, C11, h, level + 1, live);                      // C11 <- Q6 = A22 * S6
+            ew(S_POST, C21, C21, C11, -1, live, h);                    // C21 = U2 - Q6
+            mul(A12, B21, C11, h, level + 1, live);                    // C11 <- Q1 = A12 * B21
+            ew(S_POST, C11, X, C11, +1, live, h);                      // C11 = Q0 + Q1
         }
         used = mark;
     }
@@ -318,36 +468,41 @@ static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, i
     }
 
     Exec ex;
-    ex.stream = stream;
     ex.ws = (char*)ws;
     ex.ws_bytes = ws_bytes;
     ex.sched = schedule;
     ex.levels = levels;
+    const int64_t q = (int64_t)1 << levels;
+    const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
     {
-        // spend what the workspace has beyond the minimum on the rich form of the deepest DFS steps
-        const int64_t q = (int64_t)1 << levels;
-        const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
+        // spend what the workspace has beyond the minimum: first on a second set of the buffers next to the
+        // leaves (so that additions and leaf products of consecutive launches overlap), then on the rich form
+        // of the deepest DFS steps
         const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
-        ex.rich = choose_rich(nrec, levels, schedule, ws_bytes - fixed);
+        choose_options(nrec, levels, schedule, ws_bytes - fixed, g_overlap != 0, &ex.rich, &ex.dbl);
     }
     ex.prof = profiler();
+    ex.sc.start(stream, g_overlap != 0 && levels > 0);
+    set_add_block_cap(ex.sc.multi ? g_overlap : 0);
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
-    const int64_t r = n % ((int64_t)1 << levels);
+    const int64_t r = n % q;
     if (r != 0 && g_odd_mode == SW_ODD_PEEL) {
         // Peeling (Section 3.1 names it beside padding): the leading n0 x n0 blocks, n0 the previous multiple
         // of 2^levels, go through the recursion in place; the r < 2^levels peeled rows and columns are
         // finished by three thin classical products on the same MFMA kernel.
         const int64_t n0 = n - r;
         ex.mul(a, b, c, n0, 0, 1);                                   // C11  = A11 * B11
-        prof_begin(ex.prof, stream, SW_CLASS_PEEL, 2.0 * r * ((double)n0 * n0 + 2.0 * (double)n * n0 + (double)n * r));
         const Mat a12{a.p + n0, lda, 0}, b21{b.p + n0 * ldb, ldb, 0};
-        ex.note(launch_gemm(n0, n0, r, 1, a12, b21, c, true, stream));                        // C11 += A12 * B21
         const Mat bright{b.p + n0, ldb, 0}, c12{c.p + n0, ldc, 0};
-        ex.note(launch_gemm(n0, r, n, 1, a, bright, c12, false, stream));                     // C12  = [A11 A12] * [B12; B22]
         const Mat abot{a.p + n0 * lda, lda, 0}, cbot{c.p + n0 * ldc, ldc, 0};
-        ex.note(launch_gemm(r, n, n, 1, abot, b, cbot, false, stream));                       // [C21 C22] = [A21 A22] * B
-        prof_end(ex.prof, stream);
+        ex.op(S_POST, SW_CLASS_PEEL, 2.0 * r * ((double)n0 * n0 + 2.0 * (double)n * n0 + (double)n * r),
+              {rng(a, n, n), rng(b, n, n)}, {rng(c, n, n)}, [&](hipStream_t st) {
+                  hipError_t e1 = launch_gemm(n0, n0, r, 1, a12, b21, c, true, st);          // C11 += A12 * B21
+                  hipError_t e2 = launch_gemm(n0, r, n, 1, a, bright, c12, false, st);       // C12  = [A11 A12] * [B12; B22]
+                  hipError_t e3 = launch_gemm(r, n, n, 1, abot, b, cbot, false, st);         // [C21 C22] = [A21 A22] * B
+                  return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
+              });
     } else {
         const int64_t np = padded_n(n, levels);
         if (np != n) {
@@ -356,18 +511,24 @@ static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, i
             a = Mat{ex.take(e), ld, 0, ld > np};
             b = Mat{ex.take(e), ld, 0, ld > np};
             c = Mat{ex.take(e), ld, 0, ld > np};
-            prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np));
-            ex.note(launch_pad_copy(A, lda, n, n, a.p, ld, np, np, stream));
-            ex.note(launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, stream));
-            prof_end(ex.prof, stream);
+            const Mat ua{const_cast<double*>(A), lda, 0}, ub{const_cast<double*>(B), ldb, 0};
+            ex.op(S_PRE, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np), {rng(ua, n, n), rng(ub, n, n)},
+                  {rng(a, np, np), rng(b, np, np)}, [&](hipStream_t st) {
+                      hipError_t e1 = launch_pad_copy(A, lda, n, n, a.p, ld, np, np, st);
+                      hipError_t e2 = launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, st);
+                      return e1 != hipSuccess ? e1 : e2;
+                  });
         }
         ex.mul(a, b, c, np, 0, 1);
         if (np != n) {
-            prof_begin(ex.prof, stream, SW_CLASS_PAD, 8.0 * 2.0 * n * n);
-            ex.note(launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, stream));
-            prof_end(ex.prof, stream);
+            const Mat uc{C, ldc, 0};
+            ex.op(S_POST, SW_CLASS_PAD, 8.0 * 2.0 * n * n, {rng(c, np, np)}, {rng(uc, n, n)},
+                  [&](hipStream_t st) { return launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, st); });
         }
     }
+    ex.sc.finish();
+    set_add_block_cap(0);
+    ex.note(ex.sc.err);
     if (ex.err != hipSuccess) return hip_fail(ex.err, "kernel launch");
     return SW_OK;
 }
@@ -494,8 +655,10 @@ int64_t sw_plan_workspace(int64_t n, int levels, const char* schedule, int64_t b
     const int64_t q = (int64_t)1 << levels;
     const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
     const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
-    const uint32_t rich = choose_rich(nrec, levels, schedule, budget_bytes - fixed);
-    return fixed + ws_need_bytes(nrec, schedule, 1, rich);
+    uint32_t rich = 0;
+    bool dbl = false;
+    choose_options(nrec, levels, schedule, budget_bytes - fixed, g_overlap != 0, &rich, &dbl);
+    return fixed + ws_need_bytes(nrec, schedule, 1, rich, dbl);
 }
 
 int sw_plan_schedule(int64_t n, int levels, int64_t budget_bytes, char* out)
@@ -549,6 +712,13 @@ int sw_set_workspace(void* dev_ptr, int64_t bytes)
     if ((uintptr_t)dev_ptr & 255u) { set_error("workspace must be 256-byte aligned"); return SW_EINVAL; }
     g_ws = dev_ptr;
     g_ws_bytes = bytes;
+    return SW_OK;
+}
+
+int sw_set_overlap(int on)
+{
+    if (on < 0) { set_error("negative argument"); return SW_EINVAL; }
+    g_overlap = on == 1 ? 256 : on;
     return SW_OK;
 }
 

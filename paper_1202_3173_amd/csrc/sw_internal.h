@@ -43,26 +43,39 @@ inline bool fuse_two_bfs(const char* sched)
 // rich: bit i set = the DFS step at level `level + i` keeps its four non-trivial T, four S and seven Q (15
 // buffers per parent, the storage of a BFS step without the plain copies) while still solving the seven
 // subproblems in sequence; its additions are then the one-pass BFS kernels.  0 = the minimum.
-inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live, uint32_t rich = 0)
+// dbl: the buffers of the step whose children are the leaves exist twice (consecutive leaf launches then
+// alternate between the two sets, so the additions of one launch overlap the products of another).
+inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live, uint32_t rich = 0, bool dbl = false)
 {
     if (*sched == '\0') return 0;
     const int64_t h = n / 2;
     const int64_t e = ws_mat_elems(h) * (int64_t)sizeof(double);
     if (fuse_two_bfs(sched)) {
         const int64_t e4 = ws_mat_elems(h / 2) * (int64_t)sizeof(double);
-        return 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live, rich >> 2);
+        const int copies = (dbl && sched[2] == '\0') ? 2 : 1;
+        return copies * 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live, rich >> 2, dbl);
     }
-    if (*sched == 'B') return 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live, rich >> 1);
-    return ((rich & 1u) ? 15 : 2) * live * e + ws_need_bytes(h, sched + 1, live, rich >> 1);
+    if (*sched == 'B') {
+        const int copies = (dbl && sched[1] == '\0') ? 2 : 1;
+        return copies * 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live, rich >> 1, dbl);
+    }
+    return ((rich & 1u) ? 15 : 2) * live * e + ws_need_bytes(h, sched + 1, live, rich >> 1, dbl);
 }
 
-// Which DFS steps get the rich form for a workspace of `budget` bytes: deepest first, while it fits.
-inline uint32_t choose_rich(int64_t n, int levels, const char* sched, int64_t budget)
+// What to spend a workspace of `budget` bytes on beyond the minimum: first the second set of leaf-side
+// buffers (only useful when the leaves are reached more than once, i.e. below some DFS step, and when
+// additions and products run on separate streams), then the rich form of DFS steps, deepest first.
+inline void choose_options(int64_t n, int levels, const char* sched, int64_t budget, bool overlap, uint32_t* rich,
+                           bool* dbl)
 {
-    uint32_t rich = 0;
+    *rich = 0;
+    *dbl = false;
+    bool any_dfs = false;
+    for (int i = 0; i < levels; ++i) any_dfs = any_dfs || sched[i] == 'D';
+    if (overlap && any_dfs && levels > 0 && sched[levels - 1] == 'B' && ws_need_bytes(n, sched, 1, 0, true) <= budget)
+        *dbl = true;
     for (int i = levels - 1; i >= 0; --i)
-        if (sched[i] == 'D' && ws_need_bytes(n, sched, 1, rich | (1u << i)) <= budget) rich |= 1u << i;
-    return rich;
+        if (sched[i] == 'D' && ws_need_bytes(n, sched, 1, *rich | (1u << i), *dbl) <= budget) *rich |= 1u << i;
 }
 
 inline int64_t padded_n(int64_t n, int levels)
@@ -103,6 +116,10 @@ inline Mat quad(const Mat& m, int64_t h, int i, int j)
 inline Mat ws_mat(double* p, int64_t h) { return Mat{p, ws_ld(h), ws_mat_elems(h), ws_ld(h) > h}; }
 
 // ---- kernel launchers (each validates nothing: callers pass consistent shapes) --------------------------------
+
+// At most `cap` workgroups per launch of an addition kernel (0: one per logical block).  With a cap the kernels
+// become persistent streaming kernels that occupy little of each CU, for running beside the leaf products.
+void set_add_block_cap(int cap);
 
 // BFS pre-additions, Appendix A columns 1 (side 0, T from A) and 2 (side 1, S from B).
 // copies: write all seven operands (slot 7p + j); otherwise only the four non-trivial ones (slot 4p + 0..3).

@@ -321,6 +321,33 @@ def test_side_stream_and_profile_record(oracle):
     assert all(v["ms"] > 0 for k, v in prof.items() if v["launches"])
 
 
+@pytest.mark.parametrize("n,levels,sched", [(1200, 4, "DDBB"), (1000, 3, "DBD"), (768, 3, "DDB"), (1536, 3, "DBB"), (640, 2, "DD")])
+def test_three_stream_overlap_gives_the_same_bits_as_one_stream(oracle, n, levels, sched):
+    # additions and leaf products on separate streams, ordered by tracked address ranges: any missed
+    # dependency would show as a difference from the one-stream result (or between repeated runs)
+    A = inputs.matrix(n, 7000 + n, 0, "uniform")
+    B = inputs.matrix(n, 7000 + n, 1, "uniform")
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    results = {}
+    try:
+        for overlap in (False, True):
+            sw.sw_set_overlap(overlap)
+            for budget in (sw.sw_plan_memory(n, levels, sched), 10 ** 11):       # minimum, and everything it can use
+                ws = torch.empty(sw.sw_plan_workspace(n, levels, sched, budget), dtype=torch.uint8, device=DEV)
+                for rep in range(3):
+                    C = torch.full((n, n), float("nan"), dtype=torch.float64, device=DEV)
+                    ws.random_(0, 255)
+                    sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, sched, ws)
+                    torch.cuda.synchronize()
+                    results[(overlap, budget, rep)] = C.cpu().numpy()
+    finally:
+        sw.sw_set_overlap(True)
+    first = results[(False, sw.sw_plan_memory(n, levels, sched), 0)]
+    assert float(np.max(np.abs(first - oracle.gemm(A, B, levels)))) <= tol(n, A, B)
+    for key, val in results.items():
+        assert np.array_equal(val, first), key
+
+
 def test_product_can_be_captured_in_a_hip_graph_and_replayed(oracle):
     # the library allocates nothing, records no memset and never synchronises, so a caller may capture it;
     # every replay, with eager work of the program in between, must reproduce the eager result

@@ -117,7 +117,16 @@ def test_plan_workspace_spends_extra_memory_on_the_deepest_dfs_steps():
     n5 = 94080
     left = 288 * 2 ** 30 - 3 * n5 * n5 * 8 - 4 * 2 ** 30
     got = sw.sw_plan_workspace(n5, 5, "DDDBB", left)
-    assert got == sw.sw_plan_memory(n5, 5, "DDDBB") + 13 * elems(11760) * 8
+    twice = 3 * 49 * elems(2940) * 8            # first a second set of the 49 leaf operands and products ...
+    assert got == sw.sw_plan_memory(n5, 5, "DDDBB") + twice + 13 * elems(11760) * 8     # ... then the rich level-2 step
+    sw.sw_set_overlap(False)
+    try:
+        assert sw.sw_plan_workspace(n5, 5, "DDDBB", left) == sw.sw_plan_memory(n5, 5, "DDDBB") + 13 * elems(11760) * 8
+    finally:
+        sw.sw_set_overlap(True)
+    # a second set is pointless without a DFS step above (one launch) or when the leaves hang under a DFS step
+    assert sw.sw_plan_workspace(4096, 3, "BBB", 10 ** 11) == sw.sw_plan_memory(4096, 3, "BBB")
+    assert sw.sw_plan_workspace(1024, 2, "DB", 10 ** 10) == (15 * elems(512) + 2 * 21 * elems(256)) * 8
 
 
 def test_peel_mode_needs_no_copies():
