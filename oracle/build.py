@@ -10,14 +10,17 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "sw_oracle.c")
 LIB = os.path.join(HERE, "libsw_oracle.so")
+SRC2 = os.path.join(HERE, "sw_bilinear_oracle.c")
+LIB2 = os.path.join(HERE, "libsw_bilinear_oracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
-        return LIB
-    cmd = ["gcc", "-std=c11", "-O3", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-           "-Wall", "-Wextra", "-o", LIB, SRC]
-    subprocess.run(cmd, check=True)
+    for src, lib in ((SRC, LIB), (SRC2, LIB2)):
+        if not force and os.path.exists(lib) and os.path.getmtime(lib) >= os.path.getmtime(src):
+            continue
+        cmd = ["gcc", "-std=c11", "-O3", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", lib, src]
+        subprocess.run(cmd, check=True)
     return LIB
 
 
