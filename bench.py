@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
     ap.add_argument("--overlap", type=int, default=None, help="0: one stream; k > 0: three streams, addition kernels capped at k workgroups")
+    ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
+                    help="the 2 x 2 block scheme under the recursion (Section 6.5); default: the Strassen-Winograd path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -103,15 +105,33 @@ def main():
     A, B = inputs.device_pair(cfg, dev)
     C = torch.empty((n, n), dtype=torch.float64, device=dev)
     free, total_mem = torch.cuda.mem_get_info()
-    schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, int(free - (2 << 30)))
-    if levels == 0:
-        schedule = ""
-    need = sw.sw_plan_workspace(n, levels, schedule, int(free - (2 << 30)))   # the minimum plus what the library can use
+    budget = int(free - (2 << 30))
+    scheme = {"winograd": sw.SW_SCHEME_WINOGRAD, "strassen": sw.SW_SCHEME_STRASSEN, "classical": sw.SW_SCHEME_CLASSICAL}[args.scheme]
+    if scheme == sw.SW_SCHEME_WINOGRAD:
+        schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, budget)
+        if levels == 0:
+            schedule = ""
+        need = sw.sw_plan_workspace(n, levels, schedule, budget)   # the minimum plus what the library can use
+    else:
+        # the comparison schemes: most BFS steps that fit, then least memory (the library's own preference)
+        orders = ["".join("B" if (mask >> i) & 1 else "D" for i in range(levels)) for mask in range(1 << levels)]
+        fits = [(-o.count("B"), sw.sw_plan_memory_bilinear(n, levels, o, scheme), o) for o in orders]
+        fits = [f for f in fits if f[1] <= budget and 8 ** -f[0] <= 4096]
+        if args.schedule is None and not fits:
+            sys.exit("bench.py: no step order of this scheme fits the free device memory")
+        schedule = args.schedule if args.schedule is not None else min(fits)[2]
+        need = sw.sw_plan_memory_bilinear(n, levels, schedule, scheme)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
+    if scheme != sw.SW_SCHEME_WINOGRAD:
+        sw.sw_set_workspace(ws)
+        sw.sw_set_stream(stream)
 
     def step():
-        sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, ws, stream)
+        if scheme == sw.SW_SCHEME_WINOGRAD:
+            sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, ws, stream)
+        else:
+            sw.sw_gemm_bilinear(n, A, B, C, levels, schedule, scheme)
 
     for _ in range(args.warmup):
         step()
@@ -129,7 +149,7 @@ def main():
     eff_gflops = 2.0 * n ** 3 / (dt / args.steps) / 1e9
 
     leaf = prof["leaf_gemm"]
-    leaf_batch = 7 ** schedule.count("B")            # leaves per launch: the batch grows sevenfold at every BFS step
+    leaf_batch = (8 if args.scheme == "classical" else 7) ** schedule.count("B")   # leaves per launch
     leaf_tflops = leaf["work"] / (leaf["ms"] * 1e-3) / 1e12 if leaf["ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": "leaf_gemm_kernel (batched fp64 MFMA)",
                 "achieved": round(leaf_tflops, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -162,13 +182,14 @@ def main():
         "metric": "effective fp64 GFLOP/s (2n^3/t)", "value": round(eff_gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": f"{cfg['name']}: n={n} square fp64 C=A*B, {levels} Strassen-Winograd levels, "
+        "config": {"workload": f"{cfg['name']}: n={n} square fp64 C=A*B, {levels} "
+                               + {"winograd": "Strassen-Winograd", "strassen": "Strassen (original)", "classical": "recursive classical"}[args.scheme] + " levels, "
                                f"leaf {n >> levels}, entries {cfg['dist']} seed {cfg['seed']}"
                                + (f", odd size handled by {args.odd_mode}" if n % (1 << levels) else ""),
                    "n": n, "levels": levels, "schedule": schedule, "workspace_GB": round(need / 1e9, 3),
                    "hbm_total_GB": round(total_mem / 1e9, 1)},
         "pct_of_fp64_mfma_peak": round(100.0 * eff_gflops / (FP64_MFMA_PEAK_TFLOPS * 1e3), 2),
-        "actual_flops_per_step": sw.sw_flop_count(n, levels) if n % (1 << levels) == 0 else None,
+        "actual_flops_per_step": sw.sw_flop_count_bilinear(n, levels, scheme) if n % (1 << levels) == 0 else None,
         "roofline": roofline,
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
                       "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds},
@@ -177,7 +198,7 @@ def main():
         "paper_context": "Cray XT4: 49.1 effective GFLOPS/node, 33% above the classical peak (Section 5.2)",
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(n, levels)
+        out["cpu_baseline"] = cpu_baseline(n, levels)     # always the Strassen-Winograd oracle
     print(json.dumps(out))
     if check > tol:
         sys.exit(1)

@@ -15,7 +15,8 @@ SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
-           "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read")
+           "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
+           "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear")
 
 
 class SwError(RuntimeError):
@@ -42,6 +43,9 @@ def lib():
         "sw_plan_memory": (i64, [i64, ci, cp]),
         "sw_gemm_scaled": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
+        "sw_gemm_bilinear": (ci, [i64, vp, vp, vp, ci, cp, ci]),
+        "sw_plan_memory_bilinear": (i64, [i64, ci, cp, ci]),
+        "sw_flop_count_bilinear": (dbl, [i64, ci, ci]),
         "sw_plan_workspace": (i64, [i64, ci, cp, i64]),
         "sw_plan_schedule": (ci, [i64, ci, i64, ctypes.c_char_p]),
         "sw_model_words": (i64, [i64, ci, cp]),
@@ -177,6 +181,26 @@ def sw_gemm_scaled(n, A, B, C, levels, schedule, scaling):
 
 def sw_plan_memory_scaled(n, levels, schedule=None):
     return _check(lib().sw_plan_memory_scaled(n, levels, _sched(schedule)))
+
+
+SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL = 0, 1, 2
+
+
+def sw_gemm_bilinear(n, A, B, C, levels, schedule, scheme):
+    """C = A @ B by the recursion of another 2 x 2 block scheme (Section 6.5) through the library state."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+        if not t.is_contiguous() or tuple(t.shape) != (n, n):
+            raise ValueError(f"{name} must be a contiguous {n} x {n} tensor")
+    return _check(lib().sw_gemm_bilinear(n, _ptr(A), _ptr(B), _ptr(C), levels, _sched(schedule), scheme))
+
+
+def sw_plan_memory_bilinear(n, levels, schedule, scheme):
+    return _check(lib().sw_plan_memory_bilinear(n, levels, _sched(schedule), scheme))
+
+
+def sw_flop_count_bilinear(n, levels, scheme):
+    return lib().sw_flop_count_bilinear(n, levels, scheme)
 
 
 def sw_gemm_ex(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, stream_handle=None):

@@ -39,6 +39,13 @@ static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divid
 static int g_overlap = 256;           // > 0: additions and leaf products on separate streams, the addition
                                       // kernels then run with at most this many workgroups; 0: one stream
 
+void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream)
+{
+    *ws = g_ws;
+    *ws_bytes = g_ws_bytes;
+    *stream = g_stream;
+}
+
 // ---- profiling ------------------------------------------------------------------------------------------------
 
 struct Profiler {
@@ -75,7 +82,7 @@ void prof_end(Profiler* p, hipStream_t s)
 
 // ---- schedule checks and the planner ------------------------------------------------------------------------------
 
-static bool schedule_ok(const char* s, int levels)
+bool schedule_ok(const char* s, int levels)
 {
     if ((int)strlen(s) != levels) return false;
     for (int i = 0; i < levels; ++i)
@@ -83,7 +90,7 @@ static bool schedule_ok(const char* s, int levels)
     return true;
 }
 
-static int check_shape(int64_t n, int levels)
+int check_shape(int64_t n, int levels)
 {
     if (n < 0 || levels < 0 || levels > SW_MAX_LEVELS) {
         set_error("bad shape: n = %lld, levels = %d (0 <= levels <= %d)", (long long)n, levels, SW_MAX_LEVELS);
@@ -423,7 +430,7 @@ struct Exec {
     }
 };
 
-static bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
+bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
 {
     const uintptr_t a0 = (uintptr_t)p, a1 = a0 + (uintptr_t)pn * sizeof(double);
     const uintptr_t b0 = (uintptr_t)q, b1 = b0 + (uintptr_t)qn * sizeof(double);

@@ -89,6 +89,13 @@ inline int64_t padded_n(int64_t n, int levels)
 void set_error(const char* fmt, ...);
 int hip_fail(hipError_t e, const char* what);
 
+// ---- argument checks and library state shared by the entry points ------------------------------------------------
+
+bool schedule_ok(const char* s, int levels);           // `levels` characters, each B or D
+int check_shape(int64_t n, int levels);                // SW_OK or SW_EINVAL with the error text set
+bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn);   // element ranges [p, p+pn) and [q, q+qn)
+void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream);     // what sw_set_workspace / sw_set_stream left
+
 // ---- profiling record (sw_profile_enable / sw_profile_read) ---------------------------------------------------
 
 struct Profiler;

@@ -1,0 +1,130 @@
+"""Other 2 x 2 block schemes on the BFS/DFS machinery (Section 6.5) on the GPU against the bilinear oracle.
+
+Bar as for the main path: within 1e-10 * n * max|A| * max|B| on real inputs (the leaf products sum in another
+order than the oracle's), bit for bit on integer-valued inputs, and no dependence on the BFS/DFS order at all.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_1202_3173_amd import binding as sw
+from paper_1202_3173_amd import inputs
+
+sys.path.insert(0, os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle"))
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ORACLE_SCHEME = {sw.SW_SCHEME_STRASSEN: 0, sw.SW_SCHEME_CLASSICAL: 1}
+
+
+@pytest.fixture(scope="module")
+def bil(oracle):
+    import sw_bilinear
+    sw_bilinear.lib()
+    return sw_bilinear
+
+
+def run(A, B, levels, schedule, scheme, slack=0):
+    n = A.shape[0]
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.full((n, n), float("nan"), dtype=torch.float64, device=DEV)
+    need = sw.sw_plan_memory_bilinear(n, levels, schedule, scheme)
+    ws = torch.empty(max(need + slack, 256), dtype=torch.uint8, device=DEV)
+    sw.sw_set_workspace(ws)
+    sw.sw_set_stream(torch.cuda.current_stream().cuda_stream)
+    try:
+        sw.sw_gemm_bilinear(n, dA, dB, C, levels, schedule, scheme)
+        torch.cuda.synchronize()
+    finally:
+        sw.sw_set_workspace(None)
+        sw.sw_set_stream(0)
+    assert torch.equal(dA.cpu(), torch.from_numpy(A)) and torch.equal(dB.cpu(), torch.from_numpy(B)), "inputs changed"
+    return C.cpu().numpy()
+
+
+CASES = [(2, 1, "B"), (2, 1, "D"), (64, 2, "BD"), (96, 3, "DBD"), (264, 2, "DD"), (520, 3, "BBB"), (1000, 2, "DB"),
+         (333, 2, "BD"), (777, 3, "DDB"), (1536, 4, "DBDB")]
+
+
+@pytest.mark.parametrize("scheme", [sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_CLASSICAL])
+@pytest.mark.parametrize("n,levels,schedule", CASES)
+def test_integer_products_bit_exact(bil, scheme, n, levels, schedule):
+    A = inputs.matrix(n, 70 + n, 0, "integer")
+    B = inputs.matrix(n, 70 + n, 1, "integer")
+    got = run(A, B, levels, schedule, scheme)
+    exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    assert np.array_equal(got, exact)
+    if n % (1 << levels) == 0 and n <= 520:
+        assert np.array_equal(got, bil.gemm(A, B, levels, ORACLE_SCHEME[scheme]))
+
+
+@pytest.mark.parametrize("scheme", [sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_CLASSICAL])
+@pytest.mark.parametrize("n,levels,schedule", [(64, 2, "BD"), (520, 3, "BBB"), (520, 3, "DDD"), (1024, 3, "DBD"), (1000, 2, "DB")])
+def test_real_products_within_tolerance(bil, scheme, n, levels, schedule):
+    A = inputs.matrix(n, 5 + n, 0, "uniform")
+    B = inputs.matrix(n, 5 + n, 1, "rowscaled")
+    got = run(A, B, levels, schedule, scheme)
+    if n % (1 << levels) == 0:
+        ref = bil.gemm(A, B, levels, ORACLE_SCHEME[scheme])
+    else:   # the oracle takes multiples of 2^levels only: zero padding does not change the product
+        npad = -(-n // (1 << levels)) * (1 << levels)
+        Ap = np.zeros((npad, npad)); Ap[:n, :n] = A
+        Bp = np.zeros((npad, npad)); Bp[:n, :n] = B
+        ref = bil.gemm(Ap, Bp, levels, ORACLE_SCHEME[scheme])[:n, :n]
+    bar = 1e-10 * n * float(np.max(np.abs(A))) * float(np.max(np.abs(B)))
+    assert np.max(np.abs(got - ref)) <= bar
+    if scheme == sw.SW_SCHEME_CLASSICAL:
+        # the recursive classical algorithm keeps the component-wise bound of the classical one (Section 6.1)
+        exact = (A.astype(np.longdouble) @ B.astype(np.longdouble)).astype(np.float64)
+        assert np.all(np.abs(got - exact) <= n * np.finfo(float).eps * (np.abs(A) @ np.abs(B)))
+
+
+@pytest.mark.parametrize("scheme", [sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_CLASSICAL])
+def test_every_step_order_gives_the_same_bits(scheme):
+    n, levels = 448, 3
+    A = inputs.matrix(n, 8, 0, "uniform")
+    B = inputs.matrix(n, 8, 1, "uniform")
+    first = None
+    for mask in range(1 << levels):
+        schedule = "".join("B" if (mask >> i) & 1 else "D" for i in range(levels))
+        got = run(A, B, levels, schedule, scheme)
+        if first is None:
+            first = got
+        assert np.array_equal(got, first), schedule
+
+
+def test_planned_order_and_winograd_forwarding():
+    n, levels = 512, 3
+    A = inputs.matrix(n, 9, 0, "integer")
+    B = inputs.matrix(n, 9, 1, "integer")
+    exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    # schedule None: the library plans for the workspace it was given (here: room for all-BFS)
+    slack = sw.sw_plan_memory_bilinear(n, levels, "BBB", sw.SW_SCHEME_STRASSEN)
+    assert np.array_equal(run(A, B, levels, None, sw.SW_SCHEME_STRASSEN, slack=slack), exact)
+    # scheme 0 is the Strassen-Winograd product itself
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.empty((n, n), dtype=torch.float64, device=DEV)
+    ws = torch.empty(sw.sw_plan_memory(n, levels, "BDB"), dtype=torch.uint8, device=DEV)
+    sw.sw_set_workspace(ws)
+    try:
+        sw.sw_gemm_bilinear(n, dA, dB, C, levels, "BDB", sw.SW_SCHEME_WINOGRAD)
+        torch.cuda.synchronize()
+    finally:
+        sw.sw_set_workspace(None)
+    assert np.array_equal(C.cpu().numpy(), exact)
+
+
+def test_errors():
+    n = 64
+    A = torch.zeros((n, n), dtype=torch.float64, device=DEV)
+    C = torch.zeros((n, n), dtype=torch.float64, device=DEV)
+    with pytest.raises(sw.SwError) as e:
+        sw.sw_gemm_bilinear(n, A, A, C, 1, "B", 7)
+    assert e.value.code == -1
+    sw.sw_set_workspace(None)
+    with pytest.raises(sw.SwError) as e:
+        sw.sw_gemm_bilinear(n, A, A, C, 1, "B", sw.SW_SCHEME_STRASSEN)
+    assert e.value.code == -2

@@ -3,6 +3,7 @@ planner / memory / flop calls agree with the paper's formulas and with the oracl
 import math
 import os
 import re
+import sys
 
 import pytest
 
@@ -56,6 +57,7 @@ def test_plan_memory_structure():
         if ld >= 256 and ld % 256 == 0:
             ld += 16
         return (ld * h + 31) // 32 * 32
+    import sw_bilinear
     assert sw.sw_plan_memory(256, 1, "B") == 21 * elems(128) * 8
     assert sw.sw_plan_memory(256, 1, "D") == 2 * elems(128) * 8
     assert sw.sw_plan_memory(1024, 2, "DB") == (2 * elems(512) + 21 * elems(256)) * 8
@@ -102,6 +104,7 @@ def test_plan_workspace_spends_extra_memory_on_the_deepest_dfs_steps():
         if ld >= 256 and ld % 256 == 0:
             ld += 16
         return (ld * h + 31) // 32 * 32
+    import sw_bilinear
     n, L, s = 1024, 3, "DDD"
     lean = sw.sw_plan_memory(n, L, s)
     assert lean == (2 * elems(512) + 2 * elems(256) + 2 * elems(128)) * 8
@@ -161,3 +164,38 @@ def test_argument_errors_without_gpu():
         assert sw.sw_last_error() != ""
     with pytest.raises(sw.SwError):
         sw.sw_model_words(100, 3, "BBB")
+
+
+# ---- other 2 x 2 block schemes (Section 6.5) ------------------------------------------------------------------
+
+def test_bilinear_memory_and_flop_counts(oracle):
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+
+    def ws_mat_elems(h):     # the documented workspace rule: pitch a multiple of 16, never of 256; slots of 32
+        ld = (h + 15) // 16 * 16
+        ld += 16 if ld % 256 == 0 else 0
+        return (ld * h + 31) // 32 * 32
+    import sw_bilinear
+    for scheme, q, oid in ((sw.SW_SCHEME_STRASSEN, 7, 0), (sw.SW_SCHEME_CLASSICAL, 8, 1)):
+        n, levels = 1024, 3
+        # BFS step: 3q half-size buffers per parent, the parents multiply by q; DFS step: 3 per parent
+        want = 0
+        live, size = 1, n
+        for ch in "BDB":
+            size //= 2
+            want += (3 * q if ch == "B" else 3) * live * ws_mat_elems(size) * 8
+            live *= q if ch == "B" else 1
+        assert sw.sw_plan_memory_bilinear(n, levels, "BDB", scheme) == want
+        assert sw.sw_plan_memory_bilinear(n, levels, None, scheme) == sw.sw_plan_memory_bilinear(n, levels, "DDD", scheme)
+        # the operation count equals what the oracle actually performs
+        m = 64
+        A = inputs.matrix(m, 1, 0, "integer")
+        sw_bilinear.reset_counters()
+        sw_bilinear.gemm(A, A, 2, oid)
+        c = sw_bilinear.counters()
+        assert sw.sw_flop_count_bilinear(m, 2, scheme) == c["leaf_mul"] + c["leaf_add"] + c["block_add"]
+    assert sw.sw_flop_count_bilinear(4096, 3, sw.SW_SCHEME_CLASSICAL) == 2.0 * 4096 ** 3 - 4096 ** 2
+    assert sw.sw_flop_count_bilinear(4096, 3, sw.SW_SCHEME_WINOGRAD) == sw.sw_flop_count(4096, 3)
+    assert sw.sw_plan_memory_bilinear(4096, 3, "BBB", sw.SW_SCHEME_WINOGRAD) == sw.sw_plan_memory(4096, 3, "BBB")
+    with pytest.raises(sw.SwError):
+        sw.sw_plan_memory_bilinear(64, 1, "B", 9)
