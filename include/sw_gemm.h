@@ -88,6 +88,39 @@ int64_t sw_plan_memory_bilinear(int64_t n, int levels, const char* schedule, int
  * one operation per element and block addition); -1.0 for bad arguments.  Host arithmetic only. */
 double sw_flop_count_bilinear(int64_t n, int levels, int scheme);
 
+/* ---- the product as a general matrix multiply ------------------------------------------------------------- */
+
+/* C <- alpha * op(A) * op(B) + beta * C, the operation the fast algorithm replaces (Section 1), on row-major
+ * rectangular operands: op(A) is M x K, op(B) is K x N, C is M x N; transa / transb != 0 take the transpose,
+ * the stored matrix then being K x M (lda >= M) or N x K (ldb >= K).  The operands are cut into square
+ * s x s blocks; every block product runs through the Strassen-Winograd recursion (`levels` steps, `schedule`
+ * as for sw_gemm on an s x s problem) and the rows, columns and inner indices left over (fewer than s each)
+ * through the classical MFMA product.  s is floor(min(M, N, K) / j) rounded down to a multiple of 2^levels
+ * for the j in 1 .. 8 whose modelled time is least among those the workspace holds (one block recurses
+ * deepest, more blocks leave less to the classical remainders).  levels < 0: the depth is chosen with s by
+ * the same model (sw_plan_levels) for the
+ * workspace that is set (schedule is then ignored).  beta == 0: C is not read; alpha == 0 or K == 0: A and B
+ * are not read.  alpha, beta are passed by value.  Uses the workspace and stream of sw_set_workspace /
+ * sw_set_stream; a workspace of sw_plan_memory_dgemm bytes (j = 1: one s x s temporary, one more per
+ * transposed operand, and the recursion's own) always suffices.  C must not overlap A or B.
+ * Errors: SW_EINVAL (negative or > 200000 dimension, 2^levels > min(M, N, K), short leading dimension, NULL
+ * pointer, overlap, bad schedule), SW_ENOMEM, SW_EHIP. */
+int sw_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double* A, int64_t lda,
+             const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int levels, const char* schedule);
+/* Workspace bytes that suffice for sw_dgemm at an explicit depth (schedule NULL or "": all-DFS): the need of
+ * the largest block size it considers.  Host arithmetic only. */
+int64_t sw_plan_memory_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, int levels,
+                             const char* schedule);
+/* The recursion depth for an n x n product with `budget_bytes` of workspace (the cutoff question of Section
+ * 5.4.1, where five or six steps were best): the depth whose modelled time is least among those some step
+ * order fits -- leaf products at the measured rate of the MFMA kernel for the leaf size (tile fill
+ * included), additions at the measured HBM rate of the fused kernels.  0 = the classical product.  Host
+ * arithmetic only; negative = error code. */
+int sw_plan_levels(int64_t n, int64_t budget_bytes);
+/* The modelled time in seconds behind sw_plan_levels for one depth (step order: the planner's for the
+ * budget); -1.0 for bad arguments or when no step order of that depth fits.  Host arithmetic only. */
+double sw_model_seconds(int64_t n, int levels, int64_t budget_bytes);
+
 /* ---- the planner (Section 3.1: pick the step order that uses the memory there is; Sections 3.3.1, 3.4.1) - */
 
 /* Bytes of workspace sw_gemm needs beyond A, B, C for this n, depth and step order (what THIS library
@@ -200,7 +233,8 @@ int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
 #define SW_CLASS_PAD 4      /* pad / crop copies                        */
 #define SW_CLASS_PEEL 5     /* thin classical products of peeling (work = flops) */
 #define SW_CLASS_SCALE 6    /* diagonal scaling: maxima, scaled copies, unscaling */
-#define SW_NUM_CLASSES 7
+#define SW_CLASS_BLAS 7     /* sw_dgemm: block transposes and the alpha/beta folds into C */
+#define SW_NUM_CLASSES 8
 
 /* on != 0: bracket every kernel launch of sw_gemm with HIP events on the launch stream (no host sync).
  * sw_profile_read synchronises those events, adds up per class the elapsed milliseconds, the launches and

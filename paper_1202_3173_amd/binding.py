@@ -9,14 +9,15 @@ LIB_PATH = os.environ.get("SW_GEMM_LIB") or os.path.join(_HERE, "libsw_gemm.so")
 
 SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
 SW_MAX_LEVELS = 16
-CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel", "scale")
+CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel", "scale", "blas")
 SW_SCALE_OUTSIDE, SW_SCALE_INSIDE = 1, 2
 SW_ODD_PAD, SW_ODD_PEEL = 0, 1
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
-           "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear")
+           "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
+           "sw_plan_levels", "sw_model_seconds")
 
 
 class SwError(RuntimeError):
@@ -43,6 +44,10 @@ def lib():
         "sw_plan_memory": (i64, [i64, ci, cp]),
         "sw_gemm_scaled": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
+        "sw_dgemm": (ci, [ci, ci, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, cp]),
+        "sw_plan_memory_dgemm": (i64, [ci, ci, i64, i64, i64, ci, cp]),
+        "sw_plan_levels": (ci, [i64, i64]),
+        "sw_model_seconds": (dbl, [i64, ci, i64]),
         "sw_gemm_bilinear": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_bilinear": (i64, [i64, ci, cp, ci]),
         "sw_flop_count_bilinear": (dbl, [i64, ci, ci]),
@@ -181,6 +186,28 @@ def sw_gemm_scaled(n, A, B, C, levels, schedule, scaling):
 
 def sw_plan_memory_scaled(n, levels, schedule=None):
     return _check(lib().sw_plan_memory_scaled(n, levels, _sched(schedule)))
+
+
+def sw_dgemm(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, levels, schedule=None):
+    """C <- alpha * op(A) @ op(B) + beta * C on row-major CUDA float64 tensors, through the library state."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        if t is not None:
+            _f64_cuda(t, name)
+    p = lambda t: None if t is None else _ptr(t)
+    return _check(lib().sw_dgemm(int(bool(transa)), int(bool(transb)), M, N, K, float(alpha), p(A), lda, p(B), ldb,
+                                 float(beta), p(C), ldc, levels, _sched(schedule)))
+
+
+def sw_plan_memory_dgemm(transa, transb, M, N, K, levels, schedule=None):
+    return _check(lib().sw_plan_memory_dgemm(int(bool(transa)), int(bool(transb)), M, N, K, levels, _sched(schedule)))
+
+
+def sw_plan_levels(n, budget_bytes):
+    return _check(lib().sw_plan_levels(n, int(budget_bytes)))
+
+
+def sw_model_seconds(n, levels, budget_bytes):
+    return lib().sw_model_seconds(n, levels, int(budget_bytes))
 
 
 SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL = 0, 1, 2

@@ -109,7 +109,7 @@ int check_shape(int64_t n, int levels)
 
 // Total workspace bytes for (n, schedule): with padding the recursion runs on the next multiple of 2^levels
 // and needs padded copies of A, B, C; with peeling it runs in place on the previous multiple.
-static int64_t total_need(int64_t n, int levels, const char* sched)
+int64_t total_need(int64_t n, int levels, const char* sched)
 {
     if (n == 0) return 0;
     if (g_odd_mode == SW_ODD_PEEL) return ws_need_bytes(n - n % ((int64_t)1 << levels), sched, 1);
@@ -119,7 +119,7 @@ static int64_t total_need(int64_t n, int levels, const char* sched)
     return bytes;
 }
 
-static int plan(int64_t n, int levels, int64_t budget, char* out)
+int plan(int64_t n, int levels, int64_t budget, char* out)
 {
     // Enumerate all step orders.  Preference: most BFS steps (largest leaf batch per launch, fewest
     // launches), then least memory, which puts the DFS steps first (the Limited-Memory shape of Section 3.4).
@@ -437,7 +437,7 @@ bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
     return a0 < b1 && b0 < a1;
 }
 
-static int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                      int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
 {
     int rc = check_shape(n, levels);

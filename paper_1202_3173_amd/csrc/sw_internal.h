@@ -96,6 +96,14 @@ int check_shape(int64_t n, int levels);                // SW_OK or SW_EINVAL wit
 bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn);   // element ranges [p, p+pn) and [q, q+qn)
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream);     // what sw_set_workspace / sw_set_stream left
 
+// workspace bytes of the Strassen-Winograd product for this step order (with the padded copies, if any)
+int64_t total_need(int64_t n, int levels, const char* sched);
+// the planner: most BFS steps that fit `budget`, then least memory; writes levels + 1 characters
+int plan(int64_t n, int levels, int64_t budget, char* out);
+// the Strassen-Winograd product itself with explicit leading dimensions, workspace and stream (what sw_gemm_ex calls)
+int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+              int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream);
+
 // ---- profiling record (sw_profile_enable / sw_profile_read) ---------------------------------------------------
 
 struct Profiler;

@@ -4,6 +4,9 @@
   python -m paper_1202_3173_amd.kernel_bench pre_add --h 2940 --live 7       # HBM bandwidth
   python -m paper_1202_3173_amd.kernel_bench post_add --h 2940 --live 7      # HBM bandwidth
   python -m paper_1202_3173_amd.kernel_bench copy --bytes 8589934592         # torch's device copy, for scale
+  python -m paper_1202_3173_amd.kernel_bench dgemm --M 60000 --N 40000 --K 50000 --transa 1 --levels -1
+                                                                            # the general product (alpha, beta,
+                                                                            # transposes, rectangular), 2MNK/t
 
 Each kernel is launched `--iters` times between two HIP events on the launch stream; one JSON line reports
 the average duration and the achieved rate on ALGORITHMIC work: 2 m^3 flops per leaf product; for the
@@ -36,7 +39,15 @@ def _timed(fn, iters, warmup):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "copy"])
+    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "copy", "dgemm"])
+    ap.add_argument("--M", type=int, default=40000)
+    ap.add_argument("--N", type=int, default=40000)
+    ap.add_argument("--K", type=int, default=40000)
+    ap.add_argument("--transa", type=int, default=0)
+    ap.add_argument("--transb", type=int, default=0)
+    ap.add_argument("--levels", type=int, default=-1, help="dgemm: recursion depth, -1 = the library's cost model")
+    ap.add_argument("--alpha", type=float, default=1.0)
+    ap.add_argument("--beta", type=float, default=0.0)
     ap.add_argument("--m", type=int, default=2940)
     ap.add_argument("--batch", type=int, default=49)
     ap.add_argument("--h", type=int, default=2940)
@@ -68,6 +79,26 @@ def main():
         rate = flops / (ms * 1e-3) / 1e12
         out = {"kernel": "leaf_gemm", "m": m, "batch": b, "ld": ld, "avg_ms": round(ms, 4), "TFLOPs": round(rate, 2),
                "frac_of_fp64_mfma_peak": round(rate / FP64_MFMA_PEAK_TFLOPS, 4)}
+    elif args.kernel == "dgemm":
+        M, N, K = args.M, args.N, args.K
+        shape_a = (K, M) if args.transa else (M, K)
+        shape_b = (N, K) if args.transb else (K, N)
+        A = torch.rand(shape_a, dtype=torch.float64, device=dev) - 0.5
+        B = torch.rand(shape_b, dtype=torch.float64, device=dev) - 0.5
+        C = torch.rand((M, N), dtype=torch.float64, device=dev)
+        free, _ = torch.cuda.mem_get_info()
+        ws = torch.empty(int(free - (3 << 30)), dtype=torch.uint8, device=dev)
+        sw.sw_set_workspace(ws)
+        sw.sw_set_stream(torch.cuda.current_stream().cuda_stream)
+        ms = _timed(lambda: sw.sw_dgemm(args.transa, args.transb, M, N, K, args.alpha, A, shape_a[1], B, shape_b[1],
+                                        args.beta, C, N, args.levels, None), args.iters, args.warmup)
+        sw.sw_set_workspace(None)
+        eff = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        d = min(M, N, K)
+        out = {"kernel": "sw_dgemm", "M": M, "N": N, "K": K, "transa": args.transa, "transb": args.transb,
+               "levels": args.levels if args.levels >= 0 else f"auto ({sw.sw_plan_levels(d, ws.numel())} for a {d} block)",
+               "avg_ms": round(ms, 3), "achieved": round(eff, 2), "unit": "effective TFLOP/s (2MNK/t)",
+               "peak": FP64_MFMA_PEAK_TFLOPS, "frac": round(eff / FP64_MFMA_PEAK_TFLOPS, 4), "bound": "mfma"}
     elif args.kernel in ("pre_add", "post_add"):
         h, live = args.h, args.live
         n = 2 * h

@@ -199,3 +199,28 @@ def test_bilinear_memory_and_flop_counts(oracle):
     assert sw.sw_plan_memory_bilinear(4096, 3, "BBB", sw.SW_SCHEME_WINOGRAD) == sw.sw_plan_memory(4096, 3, "BBB")
     with pytest.raises(sw.SwError):
         sw.sw_plan_memory_bilinear(64, 1, "B", 9)
+
+
+def test_plan_levels_and_dgemm_memory():
+    # depth model: classical for small products, five steps at the headline size (as measured), never a
+    # depth no step order fits, and non-decreasing in n for a generous budget
+    big = 250 << 30
+    assert sw.sw_plan_levels(0, big) == 0 and sw.sw_plan_levels(512, big) == 0
+    assert sw.sw_plan_levels(94080, 95 << 30) == 5
+    assert sw.sw_plan_levels(94080, 0) == 0
+    prev = 0
+    for n in (1024, 4096, 16384, 32768, 65536, 131072):
+        L = sw.sw_plan_levels(n, big)
+        assert L >= prev
+        prev = L
+        assert sw.sw_plan_memory(n, L, None) <= big
+    # dgemm workspace: the recursion's own on the s x s block plus one temporary, one more per transposed operand
+    M, N, K, L = 5000, 3000, 4000, 3
+    s = 3000
+    inner = sw.sw_plan_memory(s, L, "DBB")
+    one = sw.sw_plan_memory_dgemm(0, 0, M, N, K, L, "DBB") - inner
+    assert one >= 8 * s * s
+    assert sw.sw_plan_memory_dgemm(1, 0, M, N, K, L, "DBB") - inner == 2 * one
+    assert sw.sw_plan_memory_dgemm(1, 1, M, N, K, L, "DBB") - inner == 3 * one
+    with pytest.raises(sw.SwError):
+        sw.sw_plan_memory_dgemm(0, 0, 64, 64, 3, 2, "BB")
