@@ -8,7 +8,10 @@ step order chosen by the planner for the free device memory), the one the headli
 effective GFLOP/s = 2 n^3 / t (Section 5.2).  One JSON line is printed, with
   roofline      the batched leaf GEMM (dominant kernel) against the fp64 matrix-core peak: actual flops
                 2 m^3 per leaf product, per launch, over the average launch time measured with HIP events
-                on the launch stream during the timed steps;
+                on the launch stream during the timed steps (where addition kernels run beside it on other
+                streams and stretch its launches);
+  single_stream one more product, outside the timed region, with everything on one stream: the same
+                kernels' undisturbed rates (leaf GEMM against the MFMA peak, additions against HBM);
   cpu_baseline  the CPU oracle timed on this host on one leaf-sized classical product and scaled through
                 the closed-form operation count (Appendix A) to the metric's unit.
 """
@@ -81,6 +84,7 @@ def main():
     ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
                     help="the 2 x 2 block scheme under the recursion (Section 6.5); default: the Strassen-Winograd path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-reference", action="store_true", help="skip the extra single-stream product after the timed steps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -145,6 +149,30 @@ def main():
     prof = sw.sw_profile_read()
     sw.sw_profile_enable(False)
 
+    # The timed steps run with the library's default executor (three streams: additions beside the leaf
+    # products), where the leaf kernel shares the machine with the addition kernels and its launches stretch.
+    # One more product on a single stream (not part of `value`) gives the same kernel's undisturbed rate.
+    alone = None
+    if scheme == sw.SW_SCHEME_WINOGRAD and levels > 0 and args.overlap != 0 and not args.no_reference:
+        sw.sw_set_overlap(0)
+        sw.sw_profile_enable(True)
+        t1 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        dt1 = time.perf_counter() - t1
+        p1 = sw.sw_profile_read()
+        sw.sw_profile_enable(False)
+        sw.sw_set_overlap(256 if args.overlap is None else args.overlap)
+        l1 = p1["leaf_gemm"]
+        a_bytes = sum(p1[k]["work"] for k in ("pre_add", "post_add", "dfs_add", "pad"))
+        a_ms = sum(p1[k]["ms"] for k in ("pre_add", "post_add", "dfs_add", "pad"))
+        alone = {"ms_per_step": round(dt1 * 1e3, 3), "effective_GFLOPs": round(2.0 * n ** 3 / dt1 / 1e9, 1),
+                 "leaf_TFLOPs": round(l1["work"] / (l1["ms"] * 1e-3) / 1e12, 3) if l1["ms"] > 0 else 0.0,
+                 "leaf_frac_of_peak": round(l1["work"] / (l1["ms"] * 1e-3) / 1e12 / FP64_MFMA_PEAK_TFLOPS, 4) if l1["ms"] > 0 else 0.0,
+                 "leaf_avg_launch_ms": round(l1["ms"] / max(1, l1["launches"]), 4),
+                 "additions_GBps": round(a_bytes / (a_ms * 1e-3) / 1e9, 1) if a_ms > 0 else 0.0,
+                 "additions_frac_of_hbm_peak": round(a_bytes / (a_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if a_ms > 0 else 0.0}
+
     ms_per_step = dt * 1e3 / args.steps
     eff_gflops = 2.0 * n ** 3 / (dt / args.steps) / 1e9
 
@@ -194,6 +222,7 @@ def main():
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
                       "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds},
         "leaf_ms_per_step": round(leaf["ms"] / args.steps, 3),
+        "single_stream": alone,
         "check": {"freivalds_max_abs_diff": check, "tolerance": tol, "ok": check <= tol},
         "paper_context": "Cray XT4: 49.1 effective GFLOPS/node, 33% above the classical peak (Section 5.2)",
     }
