@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
-    ap.add_argument("--overlap", type=int, default=None, help="0: one stream; k > 0: three streams, addition kernels capped at k workgroups")
+    ap.add_argument("--overlap", type=int, default=None, help="0: one stream; k > 0: three streams, leaf-side addition kernels capped at k workgroups (default 32)")
     ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
                     help="the 2 x 2 block scheme under the recursion (Section 6.5); default: the Strassen-Winograd path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -162,7 +162,7 @@ def main():
         dt1 = time.perf_counter() - t1
         p1 = sw.sw_profile_read()
         sw.sw_profile_enable(False)
-        sw.sw_set_overlap(256 if args.overlap is None else args.overlap)
+        sw.sw_set_overlap(1 if args.overlap is None else args.overlap)
         l1 = p1["leaf_gemm"]
         a_bytes = sum(p1[k]["work"] for k in ("pre_add", "post_add", "dfs_add", "pad"))
         a_ms = sum(p1[k]["ms"] for k in ("pre_add", "post_add", "dfs_add", "pad"))

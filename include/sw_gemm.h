@@ -167,9 +167,11 @@ int sw_set_stream(void* hip_stream);                /* hipStream_t; NULL = the n
  * that fold products into C run on three streams (the caller's and two of the library's), ordered by events
  * from the address ranges each kernel reads and writes, so HBM-bound additions overlap MFMA-bound products;
  * towards the caller the call still behaves as if everything ran on the caller's stream.  on == 0: one
- * stream.  The results are the same bits either way.  While overlapping, each addition kernel is launched as
- * a persistent streaming kernel of at most `on` workgroups (on == 1: the default of 256, one per CU), so that
- * it takes little of each CU away from the leaf products running beside it. */
+ * stream.  The results are the same bits either way.  While overlapping, the addition kernels next to the
+ * leaves (those that run beside the leaf products when the leaf-side buffers exist twice) are launched as
+ * persistent streaming kernels of at most `on` workgroups (on == 1: the default of 32), so that they take
+ * little of the machine away from the products; all other addition kernels lie on the critical path and
+ * get the whole machine. */
 int sw_set_overlap(int on);
 
 /* What sw_gemm, sw_plan_memory and sw_plan_schedule do when 2^levels does not divide n (Section 3.1:

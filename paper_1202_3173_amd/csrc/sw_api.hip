@@ -36,8 +36,8 @@ static void* g_ws = nullptr;
 static int64_t g_ws_bytes = 0;
 static hipStream_t g_stream = nullptr;
 static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divide n
-static int g_overlap = 256;           // > 0: additions and leaf products on separate streams, the addition
-                                      // kernels then run with at most this many workgroups; 0: one stream
+static int g_overlap = 32;            // > 0: additions and leaf products on separate streams, the addition kernels
+                                      // beside the leaf products then run with at most this many workgroups; 0: one stream
 
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream)
 {
@@ -299,6 +299,8 @@ struct Exec {
     uint32_t rich = 0;      // DFS levels that keep BFS-style storage (choose_options)
     bool dbl = false;       // the buffers next to the leaves exist twice and alternate between launches
     uint64_t flip = 0;
+    int cap_bg = 0, cap_fg = 0;   // workgroup caps of addition kernels: beside leaf products / on the critical path
+    bool bg = false;              // the operations being issued are the leaf-side ones of a double-buffered step
     Profiler* prof;
     hipError_t err = hipSuccess;
 
@@ -320,6 +322,7 @@ struct Exec {
     {
         if (err != hipSuccess) return;
         sc.acquire(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
+        if (sc.multi) set_add_block_cap(bg ? cap_bg : cap_fg);
         prof_begin(prof, sc.st[s], cls, work);
         note(launch(sc.st[s]));
         prof_end(prof, sc.st[s]);
@@ -359,6 +362,8 @@ struct Exec {
         // the step whose children are the leaves: with two sets of buffers, consecutive launches alternate
         if (dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels && (flip++ & 1))
             used += (fused ? 3 * 49 * live * ws_mat_elems(h / 2) : 21 * live * e) * (int64_t)sizeof(double);
+        const bool was_bg = bg;
+        bg = dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels;
         if (fused) {
             // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
             // their products go straight back; the level in between exists in registers only
@@ -426,6 +431,7 @@ struct Exec {
             mul(A12, B21, C11, h, level + 1, live);                    // C11 <- Q1 = A12 * B21
             ew(S_POST, C11, X, C11, +1, live, h);                      // C11 = Q0 + Q1
         }
+        bg = was_bg;
         used = mark;
     }
 };
@@ -490,7 +496,8 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
     }
     ex.prof = profiler();
     ex.sc.start(stream, g_overlap != 0 && levels > 0);
-    set_add_block_cap(ex.sc.multi ? g_overlap : 0);
+    set_add_block_cap(0);
+    ex.cap_bg = g_overlap;
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
     const int64_t r = n % q;
@@ -725,7 +732,7 @@ int sw_set_workspace(void* dev_ptr, int64_t bytes)
 int sw_set_overlap(int on)
 {
     if (on < 0) { set_error("negative argument"); return SW_EINVAL; }
-    g_overlap = on == 1 ? 256 : on;
+    g_overlap = on == 1 ? 32 : on;
     return SW_OK;
 }
 
