@@ -40,7 +40,8 @@ extern "C" {
 /* ---- the product (Algorithm 1; Appendix A; Sections 3.3, 3.4) ------------------------------------------- */
 
 /* C = A*B, all n x n with leading dimension n.  `levels` Strassen-Winograd steps, then classical leaves of
- * size ceil(n / 2^levels).  levels = 0 is one classical product.  If n is not a multiple of 2^levels the
+ * size ceil(n / 2^levels).  levels = 0 is one classical product; levels < 0 leaves the depth to the library
+ * (sw_plan_levels for the workspace that is set; schedule is then ignored).  If n is not a multiple of 2^levels the
  * operands are zero-padded into workspace copies of the next multiple (Section 3.1 allows padding).
  * A and B are read only; C is overwritten; C must not overlap A or B.  Uses the workspace and stream set by
  * sw_set_workspace / sw_set_stream.  schedule NULL or "": the planner's choice for the current workspace

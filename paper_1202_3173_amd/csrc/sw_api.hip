@@ -446,6 +446,12 @@ bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
 int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                      int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
 {
+    if (levels < 0) {
+        // depth left open: the cost model's choice for this workspace, step order by the planner
+        if (n < 0 || n > 200000) { set_error("bad shape: n = %lld", (long long)n); return SW_EINVAL; }
+        levels = plan_levels(n, ws ? ws_bytes : 0);
+        schedule = nullptr;
+    }
     int rc = check_shape(n, levels);
     if (rc != SW_OK) return rc;
     if (n == 0) return SW_OK;

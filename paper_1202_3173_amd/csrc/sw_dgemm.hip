@@ -319,6 +319,9 @@ int check_dims(int64_t M, int64_t N, int64_t K, int levels)
 }
 
 }  // namespace
+
+int plan_levels(int64_t n, int64_t budget) { return n > 0 ? best_levels(n, budget) : 0; }
+
 }  // namespace sw
 
 using namespace sw;

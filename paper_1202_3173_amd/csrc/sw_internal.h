@@ -100,6 +100,8 @@ void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream);     // wh
 int64_t total_need(int64_t n, int levels, const char* sched);
 // the planner: most BFS steps that fit `budget`, then least memory; writes levels + 1 characters
 int plan(int64_t n, int levels, int64_t budget, char* out);
+// the depth with the least modelled time among those some step order fits into `budget` bytes (0 < n <= 200000)
+int plan_levels(int64_t n, int64_t budget);
 // the Strassen-Winograd product itself with explicit leading dimensions, workspace and stream (what sw_gemm_ex calls)
 int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
               int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream);

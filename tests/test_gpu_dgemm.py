@@ -105,6 +105,16 @@ def test_automatic_depth():
     got, ref, _, _ = run(False, False, M, N, K, 1.0, 1.0, -1, None, extra_ws=4 << 30, exact_reference=True)
     assert np.array_equal(got, ref)
     assert sw.sw_plan_levels(8200, 3 << 30) >= 1      # so the call above did recurse
+    # the square product takes the same choice with levels < 0
+    n = 8200
+    A = rect(n, n, 5, 0, "integer")
+    B = rect(n, n, 5, 1, "integer")
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.full((n, n), float("nan"), dtype=torch.float64, device=DEV)
+    ws = torch.empty(3 << 30, dtype=torch.uint8, device=DEV)
+    sw.sw_gemm_ex(n, dA, n, dB, n, C, n, -1, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy(), A @ B)
 
 
 def test_errors():
