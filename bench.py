@@ -184,7 +184,9 @@ def main():
                 "frac": round(leaf_tflops / FP64_MFMA_PEAK_TFLOPS, 4),
                 "traffic": measured_traffic(n >> levels, leaf_batch),
                 "launches": leaf["launches"], "avg_launch_ms": round(leaf["ms"] / max(1, leaf["launches"]), 4),
-                "flops_per_launch": leaf["work"] / max(1, leaf["launches"])}
+                "flops_per_launch": leaf["work"] / max(1, leaf["launches"]),
+                "note": ("timed with the default executor: addition kernels run beside the leaf launches on other streams and "
+                         "stretch them; `single_stream` has the same kernel undisturbed" if alone else None)}
     adds = {}
     add_bytes = add_ms = 0.0
     if prof["peel"]["launches"]:
@@ -220,7 +222,9 @@ def main():
         "actual_flops_per_step": sw.sw_flop_count_bilinear(n, levels, scheme) if n % (1 << levels) == 0 else None,
         "roofline": roofline,
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
-                      "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds},
+                      "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds,
+                      "note": ("kernel time summed over streams: the leaf-side addition kernels run capped at 32 workgroups "
+                               "beside the products, so their own rate is low by design; `single_stream` has them alone" if alone else None)},
         "leaf_ms_per_step": round(leaf["ms"] / args.steps, 3),
         "single_stream": alone,
         "check": {"freivalds_max_abs_diff": check, "tolerance": tol, "ok": check <= tol},
