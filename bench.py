@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
-    ap.add_argument("--overlap", type=int, default=None, help="0: one stream; k > 0: three streams, leaf-side addition kernels capped at k workgroups (default 32)")
+    ap.add_argument("--overlap", type=int, default=None, help="0: one stream; 1 (default): three streams, leaf-side addition kernels sized to their work; k > 1: capped at k workgroups")
     ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
                     help="the 2 x 2 block scheme under the recursion (Section 6.5); default: the Strassen-Winograd path")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -168,11 +168,13 @@ int sw_set_stream(void* hip_stream);                /* hipStream_t; NULL = the n
  * that fold products into C run on three streams (the caller's and two of the library's), ordered by events
  * from the address ranges each kernel reads and writes, so HBM-bound additions overlap MFMA-bound products;
  * towards the caller the call still behaves as if everything ran on the caller's stream.  on == 0: one
- * stream.  The results are the same bits either way.  While overlapping, the addition kernels next to the
- * leaves (those that run beside the leaf products when the leaf-side buffers exist twice) are launched as
- * persistent streaming kernels of at most `on` workgroups (on == 1: the default of 32), so that they take
- * little of the machine away from the products; all other addition kernels lie on the critical path and
- * get the whole machine. */
+ * stream.  The results are the same bits either way.  Step orders without a DFS step form one chain of
+ * kernels and always run on one stream.  While overlapping, the addition kernels next to the leaves (those
+ * that run beside the leaf products when the leaf-side buffers exist twice) are launched as persistent
+ * streaming kernels with a limited number of workgroups, so that they take little of the machine away from
+ * the products: on == 1 (default) sizes that number to the work (enough to move their bytes in two thirds of
+ * the time of the leaf launch beside them, at least 32; uncapped when more than 256 would be needed),
+ * on > 1 fixes it to `on`.  All other addition kernels lie on the critical path and get the whole machine. */
 int sw_set_overlap(int on);
 
 /* What sw_gemm, sw_plan_memory and sw_plan_schedule do when 2^levels does not divide n (Section 3.1:

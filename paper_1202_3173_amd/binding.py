@@ -153,7 +153,7 @@ def sw_set_stream(stream_handle):
 
 
 def sw_set_overlap(on):
-    """False/0: one stream; True/1: three streams, leaf-side addition kernels capped at 32 workgroups; k > 1: cap k."""
+    """False/0: one stream; True/1: three streams, leaf-side addition kernels sized to their work; k > 1: capped at k workgroups."""
     return _check(lib().sw_set_overlap(int(on)))
 
 

@@ -36,8 +36,9 @@ static void* g_ws = nullptr;
 static int64_t g_ws_bytes = 0;
 static hipStream_t g_stream = nullptr;
 static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divide n
-static int g_overlap = 32;            // > 0: additions and leaf products on separate streams, the addition kernels
-                                      // beside the leaf products then run with at most this many workgroups; 0: one stream
+static int g_overlap = 1;             // 0: one stream.  > 0: additions and leaf products on separate streams (when the
+                                      // step order has a DFS step); the addition kernels beside the leaf products then
+                                      // run with a limited number of workgroups: 1 = sized to the work, k > 1 = k
 
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream)
 {
@@ -300,6 +301,7 @@ struct Exec {
     bool dbl = false;       // the buffers next to the leaves exist twice and alternate between launches
     uint64_t flip = 0;
     int cap_bg = 0, cap_fg = 0;   // workgroup caps of addition kernels: beside leaf products / on the critical path
+    int cap_fixed = 0;            // > 1: the caller's cap for the kernels beside the leaf products; else sized per step
     bool bg = false;              // the operations being issued are the leaf-side ones of a double-buffered step
     Profiler* prof;
     hipError_t err = hipSuccess;
@@ -312,6 +314,21 @@ struct Exec {
     }
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+
+    // Workgroups for the addition kernels that run beside a leaf launch: enough to move their bytes (`units`
+    // elements per parent, three kernels) in about two thirds of the time the launch takes (`per` products of
+    // size m per parent at about 70 TFLOP/s), at the 20 GB/s a resident streaming workgroup sustains beside the
+    // products; more than 256 would mean they cannot keep up anyway, then they run uncapped and the two simply
+    // take turns.  n = 94080, leaves of 2940: 0.4 TB/s needed, 32 workgroups.
+    static int leaf_side_cap(double units, int64_t live, int per, int64_t m)
+    {
+        const double bytes = 8.0 * units * (double)live;
+        const double seconds = (double)per * (double)live * 2.0 * (double)m * m * m / 70e12;
+        const double need = bytes / (0.65 * seconds);            // bytes per second
+        const double groups = need / 20e9;
+        if (groups > 256.0) return 0;
+        return groups < 32.0 ? 32 : (int)(groups + 0.5);
+    }
 
     // bytes moved by an element-wise kernel with `nin` input and `nout` output matrices of h x h
     static double bytes(int64_t live, int64_t h, int nin, int nout) { return 8.0 * live * h * h * (nin + nout); }
@@ -364,6 +381,8 @@ struct Exec {
             used += (fused ? 3 * 49 * live * ws_mat_elems(h / 2) : 21 * live * e) * (int64_t)sizeof(double);
         const bool was_bg = bg;
         bg = dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels;
+        if (bg) cap_bg = cap_fixed > 1 ? cap_fixed : leaf_side_cap(fused ? 195.0 * (h / 2) * (h / 2) : 33.0 * h * h, live,
+                                                                  fused ? 49 : 7, fused ? h / 2 : h);
         if (fused) {
             // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
             // their products go straight back; the level in between exists in registers only
@@ -501,9 +520,10 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
         choose_options(nrec, levels, schedule, ws_bytes - fixed, g_overlap != 0, &ex.rich, &ex.dbl);
     }
     ex.prof = profiler();
-    ex.sc.start(stream, g_overlap != 0 && levels > 0);
+    // with BFS steps only the kernels form one chain: nothing could overlap, so one stream it is
+    ex.sc.start(stream, g_overlap != 0 && levels > 0 && strchr(schedule, 'D') != nullptr);
     set_add_block_cap(0);
-    ex.cap_bg = g_overlap;
+    ex.cap_fixed = g_overlap;
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
     const int64_t r = n % q;
@@ -738,7 +758,7 @@ int sw_set_workspace(void* dev_ptr, int64_t bytes)
 int sw_set_overlap(int on)
 {
     if (on < 0) { set_error("negative argument"); return SW_EINVAL; }
-    g_overlap = on == 1 ? 32 : on;
+    g_overlap = on;
     return SW_OK;
 }
 
