@@ -99,8 +99,7 @@ double sw_flop_count_bilinear(int64_t n, int levels, int scheme);
  * through the classical MFMA product.  s is floor(min(M, N, K) / j) rounded down to a multiple of 2^levels
  * for the j in 1 .. 8 whose modelled time is least among those the workspace holds (one block recurses
  * deepest, more blocks leave less to the classical remainders).  levels < 0: the depth is chosen with s by
- * the same model (sw_plan_levels) for the
- * workspace that is set (schedule is then ignored).  beta == 0: C is not read; alpha == 0 or K == 0: A and B
+ * the same model (sw_plan_levels) for the workspace that is set (schedule is then ignored).  beta == 0: C is not read; alpha == 0 or K == 0: A and B
  * are not read.  alpha, beta are passed by value.  Uses the workspace and stream of sw_set_workspace /
  * sw_set_stream; a workspace of sw_plan_memory_dgemm bytes (j = 1: one s x s temporary, one more per
  * transposed operand, and the recursion's own) always suffices.  C must not overlap A or B.
@@ -236,7 +235,7 @@ int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
 #define SW_CLASS_LEAF 2     /* batched leaf GEMM                        */
 #define SW_CLASS_DFS_ADD 3  /* element-wise kernels of DFS steps        */
 #define SW_CLASS_PAD 4      /* pad / crop copies                        */
-#define SW_CLASS_PEEL 5     /* thin classical products of peeling (work = flops) */
+#define SW_CLASS_PEEL 5     /* classical products of peeling and of sw_dgemm's remainders (work = flops) */
 #define SW_CLASS_SCALE 6    /* diagonal scaling: maxima, scaled copies, unscaling */
 #define SW_CLASS_BLAS 7     /* sw_dgemm: block transposes and the alpha/beta folds into C */
 #define SW_NUM_CLASSES 8
