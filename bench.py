@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
     ap.add_argument("--overlap", type=int, default=None, help="0: one stream; 1 (default): three streams, leaf-side addition kernels sized to their work; k > 1: capped at k workgroups")
     ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
-                    help="the 2 x 2 block scheme under the recursion (Section 6.5); default: the Strassen-Winograd path")
+                    help="the 2 x 2 block scheme under the recursion (Section 6.6); default: the Strassen-Winograd path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reference", action="store_true", help="skip the extra single-stream product after the timed steps")
     args = ap.parse_args()
@@ -220,6 +220,9 @@ def main():
                    "hbm_total_GB": round(total_mem / 1e9, 1)},
         "pct_of_fp64_mfma_peak": round(100.0 * eff_gflops / (FP64_MFMA_PEAK_TFLOPS * 1e3), 2),
         "actual_flops_per_step": sw.sw_flop_count_bilinear(n, levels, scheme) if n % (1 << levels) == 0 else None,
+        # Section 6.3's yardstick: the time the algorithm's own flop count would take at the machine's peak
+        "pct_of_algorithm_peak": (round(100.0 * sw.sw_flop_count_bilinear(n, levels, scheme) / (dt / args.steps) / (FP64_MFMA_PEAK_TFLOPS * 1e12), 2)
+                                  if n % (1 << levels) == 0 else None),
         "roofline": roofline,
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
                       "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds,

@@ -65,14 +65,14 @@ int sw_gemm_scaled(int64_t n, const double* A, const double* B, double* C, int l
                    int scaling);
 int64_t sw_plan_memory_scaled(int64_t n, int levels, const char* schedule);
 
-/* ---- other recursive algorithms on the same BFS/DFS machinery (Section 6.5) ------------------------------- */
+/* ---- other recursive algorithms on the same BFS/DFS machinery (Section 6.6) ------------------------------- */
 
 /* C = A*B by a recursion built on another 2 x 2 block scheme with q products: q combinations of the quadrants
  * of A and of B are multiplied pairwise (recursively) and combined into the quadrants of C.  A BFS step keeps
  * T, S, Q of all q subproblems of every parent (3q half-size buffers), a DFS step solves them in sequence (3
  * buffers).  scheme: SW_SCHEME_WINOGRAD = sw_gemm itself; SW_SCHEME_STRASSEN = Strassen's original algorithm
  * (7 products, 18 additions per step, the count behind the constants of Section 3.3.2); SW_SCHEME_CLASSICAL =
- * the classical algorithm written recursively (8 products, 4 additions; Section 6.5.1), whose rounding errors
+ * the classical algorithm written recursively (8 products, 4 additions; Section 6.6.1), whose rounding errors
  * obey the classical component-wise bound.  Every combination is summed left to right over the quadrants 11,
  * 12, 21, 22 (over the products in their order), so all step orders give the same bits.  Same arguments,
  * state (workspace, stream), padding rule and errors as sw_gemm; the workspace must hold

@@ -1,12 +1,12 @@
 /*
  * sw_bilinear_oracle.c -- TEST INFRASTRUCTURE ONLY.
  *
- * The generalisation of Section 6.5: a recursive algorithm built from a way to multiply 2 x 2 block matrices
+ * The generalisation of Section 6.6: a recursive algorithm built from a way to multiply 2 x 2 block matrices
  * with q block products.  It forms q linear combinations of the quadrants of A and of B, multiplies them
  * pairwise (recursively), and forms the quadrants of C as linear combinations of the q products.  Two
  * schemes are tabulated here, both with coefficients in {-1, 0, +1}:
  *   scheme 0  Strassen's original algorithm (q = 7, 18 additions; the count Section 3.3.2 uses),
- *   scheme 1  the classical algorithm written recursively (q = 8, 4 additions; Section 6.5.1).
+ *   scheme 1  the classical algorithm written recursively (q = 8, 4 additions; Section 6.6.1).
  * Every combination is summed left to right over the quadrants 11, 12, 21, 22 (or over the products 0..q-1),
  * a leading -1 being a negation.  Leaf: the classical product, k ascending, multiply then add.
  * Shares no code with the HIP path.  Compile with -ffp-contract=off.

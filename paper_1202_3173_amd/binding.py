@@ -214,7 +214,7 @@ SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL = 0, 1, 2
 
 
 def sw_gemm_bilinear(n, A, B, C, levels, schedule, scheme):
-    """C = A @ B by the recursion of another 2 x 2 block scheme (Section 6.5) through the library state."""
+    """C = A @ B by the recursion of another 2 x 2 block scheme (Section 6.6) through the library state."""
     for t, name in ((A, "A"), (B, "B"), (C, "C")):
         _f64_cuda(t, name)
         if not t.is_contiguous() or tuple(t.shape) != (n, n):

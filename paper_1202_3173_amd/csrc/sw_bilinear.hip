@@ -1,10 +1,10 @@
-// Other recursive algorithms on the same machinery (Section 6.5): any way to multiply 2 x 2 block matrices with
+// Other recursive algorithms on the same machinery (Section 6.6): any way to multiply 2 x 2 block matrices with
 // q block products -- q combinations of A's quadrants, q of B's, the quadrants of C as combinations of the q
 // products -- run through the same BFS steps (all q subproblems of every parent in flight, 3q half-size
 // buffers per parent), DFS steps (one subproblem after the other, 3 buffers per parent) and batched leaf
 // products as the Strassen-Winograd path.  Two schemes are tabulated: Strassen's original algorithm (7
 // products, 18 additions) and the classical algorithm written recursively (8 products, 4 additions;
-// Section 6.5.1).  Every combination is summed left to right, so BFS and DFS steps give the same bits.
+// Section 6.6.1).  Every combination is summed left to right, so BFS and DFS steps give the same bits.
 //
 // The kernels here are generic over the coefficient table and move more data than the specialised
 // Strassen-Winograd kernels; they are the comparison algorithms, not the headline path.

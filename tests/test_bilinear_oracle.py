@@ -1,4 +1,4 @@
-"""Pins of the generic bilinear oracle (Section 6.5: any <2,2,2;q> scheme under the same recursion), no GPU."""
+"""Pins of the generic bilinear oracle (Section 6.6: any <2,2,2;q> scheme under the same recursion), no GPU."""
 import math
 import os
 import sys

@@ -1,4 +1,4 @@
-"""Other 2 x 2 block schemes on the BFS/DFS machinery (Section 6.5) on the GPU against the bilinear oracle.
+"""Other 2 x 2 block schemes on the BFS/DFS machinery (Section 6.6) on the GPU against the bilinear oracle.
 
 Bar as for the main path: within 1e-10 * n * max|A| * max|B| on real inputs (the leaf products sum in another
 order than the oracle's), bit for bit on integer-valued inputs, and no dependence on the BFS/DFS order at all.

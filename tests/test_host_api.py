@@ -166,7 +166,7 @@ def test_argument_errors_without_gpu():
         sw.sw_model_words(100, 3, "BBB")
 
 
-# ---- other 2 x 2 block schemes (Section 6.5) ------------------------------------------------------------------
+# ---- other 2 x 2 block schemes (Section 6.6) ------------------------------------------------------------------
 
 def test_bilinear_memory_and_flop_counts(oracle):
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
