@@ -285,9 +285,10 @@ def sw_profile_read():
 
 # ---- convenience on top of the ABI (allocation of the workspace with torch; no arithmetic) ---------------------
 
-def matmul(A, B, levels, schedule=None, workspace=None):
-    """C = A @ B for square float64 CUDA tensors.  Allocates C and, if none is given, a workspace of exactly
-    sw_plan_memory bytes (schedule None -> the planner's choice for 80% of the free device memory)."""
+def matmul(A, B, levels=None, schedule=None, workspace=None):
+    """C = A @ B for square float64 CUDA tensors.  Allocates C and, if none is given, a workspace: of exactly
+    sw_plan_memory bytes for a given step order, else what the planner can use of 80 % of the free device
+    memory.  levels None: the depth sw_plan_levels picks for that budget."""
     import torch
     _f64_cuda(A, "A")
     _f64_cuda(B, "B")
@@ -296,11 +297,19 @@ def matmul(A, B, levels, schedule=None, workspace=None):
     B = B.contiguous()
     C = torch.empty_like(A)
     if workspace is None:
+        free, _ = torch.cuda.mem_get_info(A.device)
+        budget = int(free * 0.8)
+        if levels is None:
+            levels = sw_plan_levels(n, budget)
+            schedule = None
         if schedule is None:
-            free, _ = torch.cuda.mem_get_info(A.device)
-            schedule = sw_plan_schedule(n, levels, int(free * 0.8))
-        need = sw_plan_memory(n, levels, schedule)
+            schedule = sw_plan_schedule(n, levels, budget)
+            need = sw_plan_workspace(n, levels, schedule, budget)
+        else:
+            need = sw_plan_memory(n, levels, schedule)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=A.device)
+    elif levels is None:
+        levels, schedule = -1, None
     with torch.cuda.device(A.device):
         sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, workspace)
     return C

@@ -115,6 +115,9 @@ def test_automatic_depth():
     sw.sw_gemm_ex(n, dA, n, dB, n, C, n, -1, None, ws)
     torch.cuda.synchronize()
     assert np.array_equal(C.cpu().numpy(), A @ B)
+    del ws
+    # and so does the convenience call that allocates C and the workspace itself
+    assert np.array_equal(sw.matmul(dA, dB).cpu().numpy(), A @ B)
 
 
 def test_errors():
