@@ -300,7 +300,7 @@ struct Exec {
     uint32_t rich = 0;      // DFS levels that keep BFS-style storage (choose_options)
     bool dbl = false;       // the buffers next to the leaves exist twice and alternate between launches
     uint64_t flip = 0;
-    int cap_bg = 0, cap_fg = 0;   // workgroup caps of addition kernels: beside leaf products / on the critical path
+    int cap_bg = 0;               // workgroup cap of the addition kernels that run beside leaf products (0: none)
     int cap_fixed = 0;            // > 1: the caller's cap for the kernels beside the leaf products; else sized per step
     bool bg = false;              // the operations being issued are the leaf-side ones of a double-buffered step
     Profiler* prof;
@@ -339,7 +339,7 @@ struct Exec {
     {
         if (err != hipSuccess) return;
         sc.acquire(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
-        if (sc.multi) set_add_block_cap(bg ? cap_bg : cap_fg);
+        if (sc.multi) set_add_block_cap(bg ? cap_bg : 0);   // kernels on the critical path get the whole machine
         prof_begin(prof, sc.st[s], cls, work);
         note(launch(sc.st[s]));
         prof_end(prof, sc.st[s]);
