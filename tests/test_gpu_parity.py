@@ -400,3 +400,38 @@ def test_argument_errors_on_device():
     Z = torch.zeros((0, 0), dtype=torch.float64, device=DEV)
     assert sw.lib().sw_gemm_ex(0, None, 0, None, 0, None, 0, 0, b"", None, 0, None) == sw.SW_OK
     assert Z.numel() == 0
+
+
+# ---- a seeded sweep over sizes, depths, step orders, odd-size modes, executors and workspace sizes ------------------
+
+def test_seeded_sweep_of_small_products_is_exact(oracle):
+    """Forty seeded combinations nobody picked by hand: integer-valued operands, so the product must equal the
+    exact integer product bit for bit whatever the size (odd ones included), depth, step order, odd-size mode
+    (pad or peel), executor (one stream or three) and workspace (the minimum, or room for the second set of
+    leaf-side buffers and the richer DFS steps)."""
+    rng = np.random.default_rng(20240229)
+    try:
+        for case in range(40):
+            levels = int(rng.integers(0, 5))
+            n = int(rng.integers(max(1 << levels, 1), 700))
+            schedule = "".join(rng.choice(["B", "D"]) for _ in range(levels))
+            peel = bool(rng.integers(0, 2))
+            overlap = bool(rng.integers(0, 2))
+            roomy = bool(rng.integers(0, 2))
+            sw.sw_set_odd_mode(sw.SW_ODD_PEEL if peel else sw.SW_ODD_PAD)
+            sw.sw_set_overlap(overlap)
+            A = inputs.matrix(n, 3000 + case, 0, "integer")
+            B = inputs.matrix(n, 3000 + case, 1, "integer")
+            need = sw.sw_plan_memory(n, levels, schedule)
+            if roomy:
+                need = sw.sw_plan_workspace(n, levels, schedule, need * 4 + (1 << 20))
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
+            dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+            C = torch.full((n, n), float("nan"), dtype=torch.float64, device=DEV)
+            sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, schedule, ws)
+            torch.cuda.synchronize()
+            exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+            assert np.array_equal(C.cpu().numpy(), exact), (case, n, levels, schedule, peel, overlap, roomy)
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+        sw.sw_set_overlap(True)
