@@ -128,3 +128,17 @@ def test_errors():
     with pytest.raises(sw.SwError) as e:
         sw.sw_gemm_bilinear(n, A, A, C, 1, "B", sw.SW_SCHEME_STRASSEN)
     assert e.value.code == -2
+
+
+def test_seeded_sweep_is_exact():
+    """Thirty seeded combinations of scheme, size (odd ones are padded), depth and step order on integers."""
+    rng = np.random.default_rng(4242)
+    for case in range(30):
+        scheme = int(rng.choice([sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_CLASSICAL]))
+        levels = int(rng.integers(0, 4))
+        n = int(rng.integers(1 << levels, 500))
+        schedule = "".join(rng.choice(["B", "D"]) for _ in range(levels))
+        A = inputs.matrix(n, 900 + case, 0, "integer")
+        B = inputs.matrix(n, 900 + case, 1, "integer")
+        exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+        assert np.array_equal(run(A, B, levels, schedule, scheme), exact), (case, scheme, n, levels, schedule)

@@ -130,3 +130,21 @@ def test_errors():
         with pytest.raises(sw.SwError) as e:
             sw.sw_dgemm(*args)
         assert e.value.code == code
+
+
+def test_seeded_sweep_of_general_products_is_exact():
+    """Thirty seeded combinations of shapes, transposes, leading-dimension padding, depths and coefficients on
+    integer-valued operands: alpha and beta are small multiples of 1/2, so every value is exact in fp64 and the
+    result must equal alpha * op(A) op(B) + beta * C bit for bit."""
+    rng = np.random.default_rng(77)
+    for case in range(30):
+        levels = int(rng.integers(0, 4))
+        lo = 1 << levels
+        M, N, K = (int(rng.integers(lo, 420)) for _ in range(3))
+        ta, tb = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        alpha = float(rng.choice([1.0, -1.0, 2.0, 0.5, 3.0]))
+        beta = float(rng.choice([0.0, 1.0, -0.5, 2.0]))
+        pads = tuple(int(x) for x in rng.integers(0, 4, size=3))
+        got, ref, _, _ = run(ta, tb, M, N, K, alpha, beta, levels, None, pads=pads, seed=500 + case, exact_reference=True,
+                             extra_ws=int(rng.integers(0, 2)) * (64 << 20))
+        assert np.array_equal(got, ref), (case, M, N, K, ta, tb, alpha, beta, levels, pads)
