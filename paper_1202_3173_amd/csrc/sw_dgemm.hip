@@ -221,11 +221,14 @@ struct Dgemm {
     void fast_block(int64_t i0, int64_t j0)
     {
         const int64_t kb = K / s, rK = K - kb * s;
+        // a single product that needs no scaling and no old C goes straight into C
+        const bool direct = alpha == 1.0 && beta == 0.0 && kb == 1 && rK == 0;
         for (int64_t k = 0; k < kb && ok(); ++k) {
             const Mat a = blockA(i0, s, k * s, s), b = blockB(k * s, s, j0, s);
             if (!ok()) return;
-            rc = gemm_impl(s, a.p, a.ld, b.p, b.ld, P, ldp, levels, schedule, rest, rest_bytes, st);
-            if (rc != SW_OK) return;
+            rc = gemm_impl(s, a.p, a.ld, b.p, b.ld, direct ? C + i0 * ldc + j0 : P, direct ? ldc : ldp, levels, schedule, rest,
+                           rest_bytes, st);
+            if (rc != SW_OK || direct) return;
             if (k == kb - 1 && rK > 0) {
                 const Mat ar = blockA(i0, s, kb * s, rK), br = blockB(kb * s, rK, j0, s);
                 classical(s, s, rK, ar, br, true);

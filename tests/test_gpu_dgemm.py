@@ -99,6 +99,13 @@ def test_beta_zero_does_not_read_c_and_alpha_zero_does_not_read_operands():
     assert np.array_equal(dC.cpu().numpy(), np.zeros((M, N)))
 
 
+@pytest.mark.parametrize("ta,tb", [(False, False), (True, True)])
+def test_unscaled_product_goes_straight_into_c(ta, tb):
+    # alpha = 1, beta = 0, one block along K: no temporary, no fold; C (NaN before, padded pitch) is simply written
+    got, ref, _, _ = run(ta, tb, 512, 768, 256, 1.0, 0.0, 2, "DB", pads=(1, 2, 3), c_nan=True)
+    assert np.array_equal(got, ref)
+
+
 def test_automatic_depth():
     # with room to spare the library picks the depth itself; whatever it picks, integers stay exact
     M, N, K = 8300, 8200, 8400
