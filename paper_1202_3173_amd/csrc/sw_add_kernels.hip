@@ -72,7 +72,7 @@ __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 // are then used in place by the caller.
 template <int SIDE, int VEC>
 __global__ void __launch_bounds__(NT)
-pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int h,
+pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int hr, int hc,
                double* __restrict__ child, int64_t cld, int64_t cstride, int copies, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
@@ -80,7 +80,7 @@ pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, 
         [=]() {
             typedef typename VecT<VEC>::type V;
             const int cx = (bx * NT + threadIdx.x) * VEC;
-            if (cx >= h) return;
+            if (cx >= hc) return;
             const int r0 = by * ROWS;
             const double* P = parent + (int64_t)bz * pstride;
             double* O = child + (int64_t)bz * (copies ? 7 : 4) * cstride;
@@ -89,19 +89,19 @@ pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, 
         #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     const double* top = P + (int64_t)row * pld + cx;
-                    const double* bot = P + (int64_t)(row + h) * pld + cx;
+                    const double* bot = P + (int64_t)(row + hr) * pld + cx;
                     q11[r] = ld<VEC>(top);
-                    q12[r] = ld<VEC>(top + h);
+                    q12[r] = ld<VEC>(top + hc);
                     q21[r] = ld<VEC>(bot);
-                    q22[r] = ld<VEC>(bot + h);
+                    q22[r] = ld<VEC>(bot + hc);
                 }
             }
         #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     double* o = O + (int64_t)row * cld + cx;
                     if (SIDE == 0) {
                         const V t2 = q21[r] + q22[r];
@@ -148,7 +148,7 @@ pre_add_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, 
 // U1 = Q0 + Q3, U2 = U1 + Q4, U3 = U1 + Q2, C11 = Q0 + Q1, C12 = U3 + Q5, C21 = U2 - Q6, C22 = U2 + Q2
 template <int VEC>
 __global__ void __launch_bounds__(NT)
-post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int h,
+post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int hr, int hc,
                 double* __restrict__ parent, int64_t pld, int64_t pstride, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
@@ -157,7 +157,7 @@ post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int 
             typedef typename VecT<VEC>::type V;
             constexpr int R = POST_ROWS;
             const int cx = (bx * NT + threadIdx.x) * VEC;
-            if (cx >= h) return;
+            if (cx >= hc) return;
             const int r0 = by * R;
             const double* q = Q + (int64_t)bz * 7 * qstride;
             double* P = parent + (int64_t)bz * pstride;
@@ -166,7 +166,7 @@ post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int 
         #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
         #pragma unroll
                     for (int j = 0; j < 7; ++j) v[r][j] = ld<VEC>(q + j * qstride + (int64_t)row * qld + cx);
                 }
@@ -174,16 +174,16 @@ post_add_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int 
         #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     const V u1 = v[r][0] + v[r][3];
                     const V u2 = u1 + v[r][4];
                     const V u3 = u1 + v[r][2];
                     double* top = P + (int64_t)row * pld + cx;
-                    double* bot = P + (int64_t)(row + h) * pld + cx;
+                    double* bot = P + (int64_t)(row + hr) * pld + cx;
                     st<VEC>(top, v[r][0] + v[r][1]);
-                    st<VEC>(top + h, u3 + v[r][5]);
+                    st<VEC>(top + hc, u3 + v[r][5]);
                     st<VEC>(bot, u2 - v[r][6]);
-                    st<VEC>(bot + h, u2 + v[r][2]);
+                    st<VEC>(bot + hc, u2 + v[r][2]);
                 }
             }
         }();
@@ -205,14 +205,14 @@ struct EwOp {
 // exactly (same element, same thread), so no __restrict__ here.
 template <int VEC, int NOPS>
 __global__ void __launch_bounds__(NT)
-ew_kernel(EwOp op0, EwOp op1, int live, int h, LGrid lg)
+ew_kernel(EwOp op0, EwOp op1, int live, int hr, int hc, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
         SW_DECODE_BLOCK(lg)
         [=]() {
             typedef typename VecT<VEC>::type V;
             const int cx = (bx * NT + threadIdx.x) * VEC;
-            if (cx >= h) return;
+            if (cx >= hc) return;
             const int r0 = by * ROWS;
             int b = bz;
             const bool second = NOPS == 2 && b >= live;
@@ -225,7 +225,7 @@ ew_kernel(EwOp op0, EwOp op1, int live, int h, LGrid lg)
         #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     xv[r] = ld<VEC>(x + (int64_t)row * op.xld + cx);
                     yv[r] = ld<VEC>(y + (int64_t)row * op.yld + cx);
                 }
@@ -233,7 +233,7 @@ ew_kernel(EwOp op0, EwOp op1, int live, int h, LGrid lg)
         #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
                 const int row = r0 + r;
-                if (row < h) st<VEC>(z + (int64_t)row * op.zld + cx, op.sign > 0 ? xv[r] + yv[r] : xv[r] - yv[r]);
+                if (row < hr) st<VEC>(z + (int64_t)row * op.zld + cx, op.sign > 0 ? xv[r] + yv[r] : xv[r] - yv[r]);
             }
         }();
     }
@@ -245,7 +245,7 @@ ew_kernel(EwOp op0, EwOp op1, int live, int h, LGrid lg)
 template <int VEC>
 __global__ void __launch_bounds__(NT)
 dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11, double* c12, double* c21,
-                double* c22, int64_t cld, int64_t cstride, int h, LGrid lg)
+                double* c22, int64_t cld, int64_t cstride, int hr, int hc, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
         SW_DECODE_BLOCK(lg)
@@ -253,7 +253,7 @@ dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11
             typedef typename VecT<VEC>::type V;
             constexpr int R = 2;
             const int cx = (bx * NT + threadIdx.x) * VEC;
-            if (cx >= h) return;
+            if (cx >= hc) return;
             const int r0 = by * R;
             const int64_t boff = (int64_t)bz * cstride;
             const double* xb = x + (int64_t)bz * xstride;
@@ -261,7 +261,7 @@ dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11
         #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     const int64_t o = boff + (int64_t)row * cld + cx;
                     q0[r] = ld<VEC>(xb + (int64_t)row * xld + cx);
                     q5[r] = ld<VEC>(c11 + o);
@@ -273,7 +273,7 @@ dfs_post_kernel(const double* x, int64_t xld, int64_t xstride, const double* c11
         #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int row = r0 + r;
-                if (row < h) {
+                if (row < hr) {
                     const int64_t o = boff + (int64_t)row * cld + cx;
                     const V u1 = q0[r] + q3[r];
                     const V u2 = u1 + q4[r];
@@ -310,7 +310,7 @@ __device__ __forceinline__ void winograd_pre(const V x11, const V x12, const V x
 
 template <int SIDE, int VEC>
 __global__ void __launch_bounds__(NT)
-pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int m,
+pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride, int mr, int mc,
                 double* __restrict__ child, int64_t cld, int64_t cstride, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
@@ -319,7 +319,7 @@ pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride,
             typedef typename VecT<VEC>::type V;
             const int cx = (bx * NT + threadIdx.x) * VEC;
             const int row = by;
-            if (cx >= m) return;
+            if (cx >= mc) return;
             const double* P = parent + (int64_t)bz * pstride + (int64_t)row * pld + cx;
             double* O = child + (int64_t)bz * 49 * cstride + (int64_t)row * cld + cx;
     
@@ -327,7 +327,7 @@ pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride,
         #pragma unroll
             for (int R = 0; R < 4; ++R)
         #pragma unroll
-                for (int C = 0; C < 4; ++C) a[R][C] = ld<VEC>(P + (int64_t)R * m * pld + C * m);
+                for (int C = 0; C < 4; ++C) a[R][C] = ld<VEC>(P + (int64_t)R * mr * pld + C * mc);
     
             V t[4][7];   // t[2p+q][j] = T_j[p][q]
         #pragma unroll
@@ -349,7 +349,7 @@ pre_add2_kernel(const double* __restrict__ parent, int64_t pld, int64_t pstride,
 // q[j][0..6] (Appendix A, fourth column) and the parent's block c[2X+p][2Y+q] the same post-addition over j.
 template <int VEC>
 __global__ void __launch_bounds__(NT)
-post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int m,
+post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int mr, int mc,
                  double* __restrict__ parent, int64_t pld, int64_t pstride, LGrid lg)
 {
     SW_LOGICAL_BLOCKS(lg) {
@@ -358,7 +358,7 @@ post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int
             typedef typename VecT<VEC>::type V;
             const int cx = (bx * NT + threadIdx.x) * VEC;
             const int row = by;
-            if (cx >= m) return;
+            if (cx >= mc) return;
             const double* q = Q + (int64_t)bz * 49 * qstride + (int64_t)row * qld + cx;
             double* P = parent + (int64_t)bz * pstride + (int64_t)row * pld + cx;
     
@@ -379,7 +379,7 @@ post_add2_kernel(const double* __restrict__ Q, int64_t qld, int64_t qstride, int
             auto put = [&](int X, int Y, const V (&c)[4]) __attribute__((always_inline)) {
         #pragma unroll
                 for (int pq = 0; pq < 4; ++pq)
-                    st<VEC>(P + (int64_t)(2 * X + (pq >> 1)) * m * pld + (2 * Y + (pq & 1)) * m, c[pq]);
+                    st<VEC>(P + (int64_t)(2 * X + (pq >> 1)) * mr * pld + (2 * Y + (pq & 1)) * mc, c[pq]);
             };
     
             V q0[4], q3[4], u1[4], u2[4], u3[4], t[4], c[4];
@@ -437,10 +437,11 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool even(int64_t v) { return (v & 1) == 0; }
 inline bool mat_vec2(const Mat& m) { return aligned16(m.p) && even(m.ld) && even(m.stride); }
 
-inline LGrid grid_for(int64_t h, int vec, int rows, int64_t batch)
+// logical grid for `batch` matrices of hr x hc: column chunks of NT * vec, groups of `rows` rows
+inline LGrid grid_for(int64_t hr, int64_t hc, int vec, int rows, int64_t batch)
 {
-    const int64_t chunks = (h + vec - 1) / vec;
-    return LGrid{(unsigned)((chunks + NT - 1) / NT), (unsigned)((h + rows - 1) / rows), (unsigned)batch};
+    const int64_t chunks = (hc + vec - 1) / vec;
+    return LGrid{(unsigned)((chunks + NT - 1) / NT), (unsigned)((hr + rows - 1) / rows), (unsigned)batch};
 }
 
 static int g_block_cap = 0;   // 0: one workgroup per logical block; else at most this many workgroups per launch
@@ -456,58 +457,58 @@ inline dim3 physical(const LGrid& lg)
 
 void set_add_block_cap(int cap) { g_block_cap = cap; }
 
-hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s)
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t hr, int64_t hc, Mat child, bool copies, hipStream_t s)
 {
-    if (live == 0 || h == 0) return hipSuccess;
-    const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(child);
-    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, live);
+    if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    const bool v2 = even(hc) && mat_vec2(parent) && mat_vec2(child);
+    const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                              \
     hipLaunchKernelGGL((pre_add_kernel<SIDE, VEC>), physical(lg), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
-                       (int)h, child.p, child.ld, child.stride, copies ? 1 : 0, lg)
+                       (int)hr, (int)hc, child.p, child.ld, child.stride, copies ? 1 : 0, lg)
     if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
     else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
 #undef SW_LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s)
+hipError_t launch_post_add(Mat q, int64_t live, int64_t hr, int64_t hc, Mat parent, hipStream_t s)
 {
-    if (live == 0 || h == 0) return hipSuccess;
-    const bool v2 = even(h) && mat_vec2(parent) && mat_vec2(q);
-    const LGrid lg = grid_for(h, v2 ? 2 : 1, POST_ROWS, live);
+    if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    const bool v2 = even(hc) && mat_vec2(parent) && mat_vec2(q);
+    const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, POST_ROWS, live);
     if (v2)
-        hipLaunchKernelGGL((post_add_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+        hipLaunchKernelGGL((post_add_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)hr, (int)hc, parent.p,
                            parent.ld, parent.stride, lg);
     else
-        hipLaunchKernelGGL((post_add_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)h, parent.p,
+        hipLaunchKernelGGL((post_add_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)hr, (int)hc, parent.p,
                            parent.ld, parent.stride, lg);
     return hipGetLastError();
 }
 
-hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat child, hipStream_t s)
+hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t mr, int64_t mc, Mat child, hipStream_t s)
 {
-    if (live == 0 || m == 0) return hipSuccess;
-    const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(child);
-    const LGrid lg = grid_for(m, v2 ? 2 : 1, 1, live);
+    if (live == 0 || mr == 0 || mc == 0) return hipSuccess;
+    const bool v2 = even(mc) && mat_vec2(parent) && mat_vec2(child);
+    const LGrid lg = grid_for(mr, mc, v2 ? 2 : 1, 1, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                               \
     hipLaunchKernelGGL((pre_add2_kernel<SIDE, VEC>), physical(lg), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, \
-                       (int)m, child.p, child.ld, child.stride, lg)
+                       (int)mr, (int)mc, child.p, child.ld, child.stride, lg)
     if (side == 0) { if (v2) SW_LAUNCH(0, 2); else SW_LAUNCH(0, 1); }
     else           { if (v2) SW_LAUNCH(1, 2); else SW_LAUNCH(1, 1); }
 #undef SW_LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStream_t s)
+hipError_t launch_post_add2(Mat q, int64_t live, int64_t mr, int64_t mc, Mat parent, hipStream_t s)
 {
-    if (live == 0 || m == 0) return hipSuccess;
-    const bool v2 = even(m) && mat_vec2(parent) && mat_vec2(q);
-    const LGrid lg = grid_for(m, v2 ? 2 : 1, 1, live);
+    if (live == 0 || mr == 0 || mc == 0) return hipSuccess;
+    const bool v2 = even(mc) && mat_vec2(parent) && mat_vec2(q);
+    const LGrid lg = grid_for(mr, mc, v2 ? 2 : 1, 1, live);
     if (v2)
-        hipLaunchKernelGGL((post_add2_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
+        hipLaunchKernelGGL((post_add2_kernel<2>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)mr, (int)mc, parent.p,
                            parent.ld, parent.stride, lg);
     else
-        hipLaunchKernelGGL((post_add2_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)m, parent.p,
+        hipLaunchKernelGGL((post_add2_kernel<1>), physical(lg), dim3(NT), 0, s, q.p, q.ld, q.stride, (int)mr, (int)mc, parent.p,
                            parent.ld, parent.stride, lg);
     return hipGetLastError();
 }
@@ -517,42 +518,42 @@ static EwOp make_op(Mat z, Mat x, Mat y, int sign)
     return EwOp{z.p, x.p, y.p, z.ld, x.ld, y.ld, z.stride, x.stride, y.stride, sign};
 }
 
-hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s)
+hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t hr, int64_t hc, hipStream_t s)
 {
-    if (live == 0 || h == 0) return hipSuccess;
-    const bool v2 = even(h) && mat_vec2(z) && mat_vec2(x) && mat_vec2(y);
-    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, live);
+    if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    const bool v2 = even(hc) && mat_vec2(z) && mat_vec2(x) && mat_vec2(y);
+    const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, live);
     const EwOp op = make_op(z, x, y, sign);
-    if (v2) hipLaunchKernelGGL((ew_kernel<2, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)h, lg);
-    else    hipLaunchKernelGGL((ew_kernel<1, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)h, lg);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)hr, (int)hc, lg);
+    else    hipLaunchKernelGGL((ew_kernel<1, 1>), physical(lg), dim3(NT), 0, s, op, op, (int)live, (int)hr, (int)hc, lg);
     return hipGetLastError();
 }
 
 hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1, int sign1, int64_t live,
-                      int64_t h, hipStream_t s)
+                      int64_t hr, int64_t hc, hipStream_t s)
 {
-    if (live == 0 || h == 0) return hipSuccess;
-    const bool v2 = even(h) && mat_vec2(z0) && mat_vec2(x0) && mat_vec2(y0) && mat_vec2(z1) && mat_vec2(x1) &&
+    if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    const bool v2 = even(hc) && mat_vec2(z0) && mat_vec2(x0) && mat_vec2(y0) && mat_vec2(z1) && mat_vec2(x1) &&
                     mat_vec2(y1);
-    const LGrid lg = grid_for(h, v2 ? 2 : 1, ROWS, 2 * live);
+    const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, 2 * live);
     const EwOp a = make_op(z0, x0, y0, sign0), b = make_op(z1, x1, y1, sign1);
-    if (v2) hipLaunchKernelGGL((ew_kernel<2, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)h, lg);
-    else    hipLaunchKernelGGL((ew_kernel<1, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)h, lg);
+    if (v2) hipLaunchKernelGGL((ew_kernel<2, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)hr, (int)hc, lg);
+    else    hipLaunchKernelGGL((ew_kernel<1, 2>), physical(lg), dim3(NT), 0, s, a, b, (int)live, (int)hr, (int)hc, lg);
     return hipGetLastError();
 }
 
-hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t h, hipStream_t s)
+hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t hr, int64_t hc, hipStream_t s)
 {
-    if (live == 0 || h == 0) return hipSuccess;
+    if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
     // the four quadrants share ld and stride by construction
-    const bool v2 = even(h) && mat_vec2(x) && mat_vec2(c11) && mat_vec2(c12) && mat_vec2(c21) && mat_vec2(c22);
-    const LGrid lg = grid_for(h, v2 ? 2 : 1, 2, live);
+    const bool v2 = even(hc) && mat_vec2(x) && mat_vec2(c11) && mat_vec2(c12) && mat_vec2(c21) && mat_vec2(c22);
+    const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, 2, live);
     if (v2)
         hipLaunchKernelGGL((dfs_post_kernel<2>), physical(lg), dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
-                           c22.p, c11.ld, c11.stride, (int)h, lg);
+                           c22.p, c11.ld, c11.stride, (int)hr, (int)hc, lg);
     else
         hipLaunchKernelGGL((dfs_post_kernel<1>), physical(lg), dim3(NT), 0, s, x.p, x.ld, x.stride, c11.p, c12.p, c21.p,
-                           c22.p, c11.ld, c11.stride, (int)h, lg);
+                           c22.p, c11.ld, c11.stride, (int)hr, (int)hc, lg);
     return hipGetLastError();
 }
 

@@ -138,22 +138,43 @@ inline Mat ws_mat(double* p, int64_t h) { return Mat{p, ws_ld(h), ws_mat_elems(h
 // become persistent streaming kernels that occupy little of each CU, for running beside the leaf products.
 void set_add_block_cap(int cap);
 
+// All addition kernels work on batches of hr x hc matrices (rows x columns); the square forms take h for both.
 // BFS pre-additions, Appendix A columns 1 (side 0, T from A) and 2 (side 1, S from B).
 // copies: write all seven operands (slot 7p + j); otherwise only the four non-trivial ones (slot 4p + 0..3).
-hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s);
+hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t hr, int64_t hc, Mat child, bool copies, hipStream_t s);
 // BFS post-additions, Appendix A column 4.
-hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s);
-// Two consecutive BFS steps in one pass: parent of size 4m -> 49 grandchildren of size m, and back.
-hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat child, hipStream_t s);
-hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStream_t s);
-// Z = X + sign * Y on h x h matrices, `live` of them; Z may be X or Y itself.
-hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s);
-// Two independent such operations in one launch (the A-side and B-side pre-addition of a DFS step).
+hipError_t launch_post_add(Mat q, int64_t live, int64_t hr, int64_t hc, Mat parent, hipStream_t s);
+// Two consecutive BFS steps in one pass: parent of 4 mr x 4 mc -> 49 grandchildren of mr x mc, and back.
+hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t mr, int64_t mc, Mat child, hipStream_t s);
+hipError_t launch_post_add2(Mat q, int64_t live, int64_t mr, int64_t mc, Mat parent, hipStream_t s);
+// Z = X + sign * Y on hr x hc matrices, `live` of them; Z may be X or Y itself.
+hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t hr, int64_t hc, hipStream_t s);
+// Two independent such operations of one shape in one launch (the A-side and B-side pre-addition of a DFS step).
 hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1, int sign1, int64_t live,
-                      int64_t h, hipStream_t s);
+                      int64_t hr, int64_t hc, hipStream_t s);
 // DFS post-addition block: with X = Q0, C12 = Q3, C21 = Q4, C22 = Q2, C11 = Q5 on entry,
 // U1 = X + C12, U2 = U1 + C21, U3 = U1 + C22, then C22 = U2 + C22, C12 = U3 + C11, C21 = U2.
-hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t h, hipStream_t s);
+hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t hr, int64_t hc, hipStream_t s);
+inline hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t h, Mat child, bool copies, hipStream_t s)
+{
+    return launch_pre_add(side, parent, live, h, h, child, copies, s);
+}
+inline hipError_t launch_post_add(Mat q, int64_t live, int64_t h, Mat parent, hipStream_t s) { return launch_post_add(q, live, h, h, parent, s); }
+inline hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t m, Mat child, hipStream_t s)
+{
+    return launch_pre_add2(side, parent, live, m, m, child, s);
+}
+inline hipError_t launch_post_add2(Mat q, int64_t live, int64_t m, Mat parent, hipStream_t s) { return launch_post_add2(q, live, m, m, parent, s); }
+inline hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h, hipStream_t s) { return launch_ew(z, x, y, sign, live, h, h, s); }
+inline hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1, int sign1, int64_t live, int64_t h,
+                             hipStream_t s)
+{
+    return launch_ew2(z0, x0, y0, sign0, z1, x1, y1, sign1, live, h, h, s);
+}
+inline hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t h, hipStream_t s)
+{
+    return launch_dfs_post(x, c11, c12, c21, c22, live, h, h, s);
+}
 // Zero-padded copy / crop.
 hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst,
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s);
