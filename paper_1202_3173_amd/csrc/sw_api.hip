@@ -110,17 +110,21 @@ int check_shape(int64_t n, int levels)
 
 // Total workspace bytes for (n, schedule): with padding the recursion runs on the next multiple of 2^levels
 // and needs padded copies of A, B, C; with peeling it runs in place on the previous multiple.
-int64_t total_need(int64_t n, int levels, const char* sched)
+static Dims padded_dims(Dims d, int levels) { return Dims{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)}; }
+
+int64_t total_need(Dims d, int levels, const char* sched)
 {
-    if (n == 0) return 0;
-    if (g_odd_mode == SW_ODD_PEEL) return ws_need_bytes(n - n % ((int64_t)1 << levels), sched, 1);
-    const int64_t np = padded_n(n, levels);
-    int64_t bytes = ws_need_bytes(np, sched, 1);
-    if (np != n) bytes += 3 * ws_mat_elems(np) * (int64_t)sizeof(double);
+    if (d.m == 0 || d.n == 0 || d.k == 0) return 0;
+    // peeling is defined for square products only (one peel at the top, three thin classical products)
+    if (g_odd_mode == SW_ODD_PEEL && d.cube()) return ws_need_bytes(d.m - d.m % ((int64_t)1 << levels), sched, 1);
+    const Dims p = padded_dims(d, levels);
+    int64_t bytes = ws_need_bytes(p, sched, 1);
+    if (p.m != d.m || p.n != d.n || p.k != d.k)
+        bytes += (ws_mat_elems(p.m, p.k) + ws_mat_elems(p.k, p.n) + ws_mat_elems(p.m, p.n)) * (int64_t)sizeof(double);
     return bytes;
 }
 
-int plan(int64_t n, int levels, int64_t budget, char* out)
+int plan(Dims d, int levels, int64_t budget, char* out)
 {
     // Enumerate all step orders.  Preference: most BFS steps (largest leaf batch per launch, fewest
     // launches), then least memory, which puts the DFS steps first (the Limited-Memory shape of Section 3.4).
@@ -135,7 +139,7 @@ int plan(int64_t n, int levels, int64_t budget, char* out)
             nb += b;
         }
         cand[levels] = '\0';
-        const int64_t need = total_need(n, levels, cand);
+        const int64_t need = total_need(d, levels, cand);
         if (need > budget) continue;
         if (nb > best_b || (nb == best_b && need < best_need)) {
             best_b = nb;
@@ -144,9 +148,9 @@ int plan(int64_t n, int levels, int64_t budget, char* out)
         }
     }
     if (best_b < 0) {
-        set_error("no step order for n = %lld, levels = %d fits a workspace of %lld bytes (all-DFS needs %lld)",
-                  (long long)n, levels, (long long)budget,
-                  (long long)total_need(n, levels, std::string((size_t)levels, 'D').c_str()));
+        set_error("no step order for %lld x %lld x %lld, levels = %d fits a workspace of %lld bytes (all-DFS needs %lld)",
+                  (long long)d.m, (long long)d.n, (long long)d.k, levels, (long long)budget,
+                  (long long)total_need(d, levels, std::string((size_t)levels, 'D').c_str()));
         return SW_ENOMEM;
     }
     return SW_OK;
@@ -320,18 +324,18 @@ struct Exec {
     // size m per parent at about 70 TFLOP/s), at the 20 GB/s a resident streaming workgroup sustains beside the
     // products; more than 256 would mean they cannot keep up anyway, then they run uncapped and the two simply
     // take turns.  n = 94080, leaves of 2940: 0.4 TB/s needed, 32 workgroups.
-    static int leaf_side_cap(double units, int64_t live, int per, int64_t m)
+    static int leaf_side_cap(double units, int64_t live, int per, Dims leaf)
     {
         const double bytes = 8.0 * units * (double)live;
-        const double seconds = (double)per * (double)live * 2.0 * (double)m * m * m / 70e12;
+        const double seconds = (double)per * (double)live * 2.0 * (double)leaf.m * (double)leaf.n * (double)leaf.k / 70e12;
         const double need = bytes / (0.65 * seconds);            // bytes per second
         const double groups = need / 20e9;
         if (groups > 256.0) return 0;
         return groups < 32.0 ? 32 : (int)(groups + 0.5);
     }
 
-    // bytes moved by an element-wise kernel with `nin` input and `nout` output matrices of h x h
-    static double bytes(int64_t live, int64_t h, int nin, int nout) { return 8.0 * live * h * h * (nin + nout); }
+    // bytes moved by a kernel with `nin` input and `nout` output matrices of r x c per parent
+    static double bytes(int64_t live, int64_t r, int64_t c, int nin, int nout) { return 8.0 * live * (double)r * (double)c * (nin + nout); }
 
     // One kernel: on stream `s`, after everything of the other streams it conflicts with.
     template <class F>
@@ -347,108 +351,128 @@ struct Exec {
         note(sc.err);
     }
 
-    // Z = X + sign * Y (stream s: S_PRE when Z is an operand of a product, S_POST when it is part of C)
-    void ew(int s, Mat z, Mat x, Mat y, int sign, int64_t live, int64_t h)
+    // Z = X + sign * Y on r x c matrices (stream s: S_PRE when Z is an operand of a product, S_POST when it is part of C)
+    void ew(int s, Mat z, Mat x, Mat y, int sign, int64_t live, int64_t r, int64_t c)
     {
-        op(s, SW_CLASS_DFS_ADD, bytes(live, h, 2, 1), {rng(x, h, h, live), rng(y, h, h, live)}, {rng(z, h, h, live)},
-           [&](hipStream_t st) { return launch_ew(z, x, y, sign, live, h, st); });
+        op(s, SW_CLASS_DFS_ADD, bytes(live, r, c, 2, 1), {rng(x, r, c, live), rng(y, r, c, live)}, {rng(z, r, c, live)},
+           [&](hipStream_t st) { return launch_ew(z, x, y, sign, live, r, c, st); });
     }
 
-    void ew2(int s, Mat z0, Mat x0, Mat y0, int s0, Mat z1, Mat x1, Mat y1, int s1, int64_t live, int64_t h)
+    // the A-side operation (on hm x hk matrices) and the B-side operation (hk x hn) of a DFS step: one launch
+    // when the two shapes coincide, else two
+    void ew2(int s, Mat z0, Mat x0, Mat y0, int s0, Mat z1, Mat x1, Mat y1, int s1, int64_t live, Dims h)
     {
-        op(s, SW_CLASS_DFS_ADD, bytes(live, h, 4, 2),
-           {rng(x0, h, h, live), rng(y0, h, h, live), rng(x1, h, h, live), rng(y1, h, h, live)},
-           {rng(z0, h, h, live), rng(z1, h, h, live)},
-           [&](hipStream_t st) { return launch_ew2(z0, x0, y0, s0, z1, x1, y1, s1, live, h, st); });
+        if (h.m != h.k || h.k != h.n) {
+            ew(s, z0, x0, y0, s0, live, h.m, h.k);
+            ew(s, z1, x1, y1, s1, live, h.k, h.n);
+            return;
+        }
+        const int64_t e = h.m;
+        op(s, SW_CLASS_DFS_ADD, bytes(live, e, e, 4, 2),
+           {rng(x0, e, e, live), rng(y0, e, e, live), rng(x1, e, e, live), rng(y1, e, e, live)},
+           {rng(z0, e, e, live), rng(z1, e, e, live)},
+           [&](hipStream_t st) { return launch_ew2(z0, x0, y0, s0, z1, x1, y1, s1, live, e, e, st); });
     }
 
-    // C = A * B for `live` independent n x n problems, steps sched[level..] (Algorithm 2: procedures DFS and BFS).
-    void mul(Mat A, Mat B, Mat C, int64_t n, int level, int64_t live)
+    // C = A * B for `live` independent problems of shape d, steps sched[level..] (Algorithm 2: procedures DFS
+    // and BFS).  With h = d / 2: operands T are h.m x h.k, S are h.k x h.n, products Q are h.m x h.n.
+    void mul(Mat A, Mat B, Mat C, Dims d, int level, int64_t live)
     {
         if (err != hipSuccess) return;
         if (level == levels) {
-            op(S_MM, SW_CLASS_LEAF, 2.0 * live * (double)n * (double)n * (double)n,
-               {rng(A, n, n, live), rng(B, n, n, live)}, {rng(C, n, n, live)},
-               [&](hipStream_t st) { return launch_leaf_gemm(n, live, A, B, C, st); });
+            op(S_MM, SW_CLASS_LEAF, 2.0 * live * (double)d.m * (double)d.n * (double)d.k,
+               {rng(A, d.m, d.k, live), rng(B, d.k, d.n, live)}, {rng(C, d.m, d.n, live)},
+               [&](hipStream_t st) { return launch_gemm(d.m, d.n, d.k, live, A, B, C, false, st); });
             return;
         }
-        const int64_t h = n / 2;
-        const int64_t e = ws_mat_elems(h);
+        const Dims h = d.half();
+        const int64_t eT = ws_mat_elems(h.m, h.k), eS = ws_mat_elems(h.k, h.n), eQ = ws_mat_elems(h.m, h.n);
         const int64_t mark = used;
         const bool fused = fuse_two_bfs(sched + level);
+        const Dims q = h.half();
+        const int64_t e4T = ws_mat_elems(q.m, q.k), e4S = ws_mat_elems(q.k, q.n), e4Q = ws_mat_elems(q.m, q.n);
         // the step whose children are the leaves: with two sets of buffers, consecutive launches alternate
         if (dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels && (flip++ & 1))
-            used += (fused ? 3 * 49 * live * ws_mat_elems(h / 2) : 21 * live * e) * (int64_t)sizeof(double);
+            used += (fused ? 49 * live * (e4T + e4S + e4Q) : 7 * live * (eT + eS + eQ)) * (int64_t)sizeof(double);
         const bool was_bg = bg;
         bg = dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels;
-        if (bg) cap_bg = cap_fixed > 1 ? cap_fixed : leaf_side_cap(fused ? 195.0 * (h / 2) * (h / 2) : 33.0 * h * h, live,
-                                                                  fused ? 49 : 7, fused ? h / 2 : h);
+        if (bg)
+            cap_bg = cap_fixed > 1 ? cap_fixed
+                                   : (fused ? leaf_side_cap(65.0 * ((double)q.m * q.k + (double)q.k * q.n + (double)q.m * q.n), live, 49, q)
+                                            : leaf_side_cap(11.0 * ((double)h.m * h.k + (double)h.k * h.n + (double)h.m * h.n), live, 7, h));
         if (fused) {
             // two BFS steps in one pass: the 49 grandchildren's operands come straight from the parents and
             // their products go straight back; the level in between exists in registers only
-            const int64_t m = h / 2;
-            const int64_t e4 = ws_mat_elems(m);
-            Mat T = ws_mat(take(49 * live * e4), m), S = ws_mat(take(49 * live * e4), m), Q = ws_mat(take(49 * live * e4), m);
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49), {rng(A, n, n, live)}, {rng(T, m, m, 49 * live)},
-               [&](hipStream_t st) { return launch_pre_add2(0, A, live, m, T, st); });
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, m, 16, 49), {rng(B, n, n, live)}, {rng(S, m, m, 49 * live)},
-               [&](hipStream_t st) { return launch_pre_add2(1, B, live, m, S, st); });
-            mul(T, S, Q, m, level + 2, 49 * live);
-            op(S_POST, SW_CLASS_POST_ADD, bytes(live, m, 49, 16), {rng(Q, m, m, 49 * live)}, {rng(C, n, n, live)},
-               [&](hipStream_t st) { return launch_post_add2(Q, live, m, C, st); });
+            Mat T = ws_mat(take(49 * live * e4T), q.m, q.k), S = ws_mat(take(49 * live * e4S), q.k, q.n),
+                Q = ws_mat(take(49 * live * e4Q), q.m, q.n);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, q.m, q.k, 16, 49), {rng(A, d.m, d.k, live)}, {rng(T, q.m, q.k, 49 * live)},
+               [&](hipStream_t st) { return launch_pre_add2(0, A, live, q.m, q.k, T, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, q.k, q.n, 16, 49), {rng(B, d.k, d.n, live)}, {rng(S, q.k, q.n, 49 * live)},
+               [&](hipStream_t st) { return launch_pre_add2(1, B, live, q.k, q.n, S, st); });
+            mul(T, S, Q, q, level + 2, 49 * live);
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, q.m, q.n, 49, 16), {rng(Q, q.m, q.n, 49 * live)}, {rng(C, d.m, d.n, live)},
+               [&](hipStream_t st) { return launch_post_add2(Q, live, q.m, q.n, C, st); });
         } else if (sched[level] == 'B') {
             // BFS step: all seven (T, S, Q) triples of every parent exist at once (Section 3.3.1)
-            Mat T = ws_mat(take(7 * live * e), h), S = ws_mat(take(7 * live * e), h), Q = ws_mat(take(7 * live * e), h);
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7), {rng(A, n, n, live)}, {rng(T, h, h, 7 * live)},
-               [&](hipStream_t st) { return launch_pre_add(0, A, live, h, T, true, st); });
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 7), {rng(B, n, n, live)}, {rng(S, h, h, 7 * live)},
-               [&](hipStream_t st) { return launch_pre_add(1, B, live, h, S, true, st); });
+            Mat T = ws_mat(take(7 * live * eT), h.m, h.k), S = ws_mat(take(7 * live * eS), h.k, h.n),
+                Q = ws_mat(take(7 * live * eQ), h.m, h.n);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h.m, h.k, 4, 7), {rng(A, d.m, d.k, live)}, {rng(T, h.m, h.k, 7 * live)},
+               [&](hipStream_t st) { return launch_pre_add(0, A, live, h.m, h.k, T, true, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h.k, h.n, 4, 7), {rng(B, d.k, d.n, live)}, {rng(S, h.k, h.n, 7 * live)},
+               [&](hipStream_t st) { return launch_pre_add(1, B, live, h.k, h.n, S, true, st); });
             mul(T, S, Q, h, level + 1, 7 * live);
-            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h, 7, 4), {rng(Q, h, h, 7 * live)}, {rng(C, n, n, live)},
-               [&](hipStream_t st) { return launch_post_add(Q, live, h, C, st); });
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h.m, h.n, 7, 4), {rng(Q, h.m, h.n, 7 * live)}, {rng(C, d.m, d.n, live)},
+               [&](hipStream_t st) { return launch_post_add(Q, live, h.m, h.n, C, st); });
         } else if (rich & (1u << level)) {
             // DFS step with the storage of a BFS step: the four non-trivial T, four S and seven Q of every
             // parent are kept, so the additions are the one-pass BFS kernels (27 instead of 38 half-size
             // matrices moved per parent), but the seven subproblems are still solved in sequence.
-            Mat Tn = ws_mat(take(4 * live * e), h), Sn = ws_mat(take(4 * live * e), h), Q = ws_mat(take(7 * live * e), h);
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4), {rng(A, n, n, live)}, {rng(Tn, h, h, 4 * live)},
-               [&](hipStream_t st) { return launch_pre_add(0, A, live, h, Tn, false, st); });
-            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h, 4, 4), {rng(B, n, n, live)}, {rng(Sn, h, h, 4 * live)},
-               [&](hipStream_t st) { return launch_pre_add(1, B, live, h, Sn, false, st); });
-            auto slot = [&](const Mat& base, int k, int per) { return Mat{base.p + k * e, base.ld, per * e, base.padded}; };
-            const Mat Ta[7] = {quad(A, h, 0, 0), quad(A, h, 0, 1), slot(Tn, 0, 4), slot(Tn, 1, 4), slot(Tn, 2, 4),
-                               slot(Tn, 3, 4), quad(A, h, 1, 1)};
-            const Mat Sb[7] = {quad(B, h, 0, 0), quad(B, h, 1, 0), slot(Sn, 0, 4), slot(Sn, 1, 4), slot(Sn, 2, 4),
-                               quad(B, h, 1, 1), slot(Sn, 3, 4)};
-            for (int j = 0; j < 7; ++j) mul(Ta[j], Sb[j], slot(Q, j, 7), h, level + 1, live);
-            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h, 7, 4), {rng(Q, h, h, 7 * live)}, {rng(C, n, n, live)},
-               [&](hipStream_t st) { return launch_post_add(Q, live, h, C, st); });
+            Mat Tn = ws_mat(take(4 * live * eT), h.m, h.k), Sn = ws_mat(take(4 * live * eS), h.k, h.n),
+                Q = ws_mat(take(7 * live * eQ), h.m, h.n);
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h.m, h.k, 4, 4), {rng(A, d.m, d.k, live)}, {rng(Tn, h.m, h.k, 4 * live)},
+               [&](hipStream_t st) { return launch_pre_add(0, A, live, h.m, h.k, Tn, false, st); });
+            op(S_PRE, SW_CLASS_PRE_ADD, bytes(live, h.k, h.n, 4, 4), {rng(B, d.k, d.n, live)}, {rng(Sn, h.k, h.n, 4 * live)},
+               [&](hipStream_t st) { return launch_pre_add(1, B, live, h.k, h.n, Sn, false, st); });
+            auto slot = [&](const Mat& base, int k, int per, int64_t e) { return Mat{base.p + k * e, base.ld, per * e, base.padded}; };
+            const Mat Ta[7] = {quad(A, h.m, h.k, 0, 0), quad(A, h.m, h.k, 0, 1), slot(Tn, 0, 4, eT), slot(Tn, 1, 4, eT),
+                               slot(Tn, 2, 4, eT), slot(Tn, 3, 4, eT), quad(A, h.m, h.k, 1, 1)};
+            const Mat Sb[7] = {quad(B, h.k, h.n, 0, 0), quad(B, h.k, h.n, 1, 0), slot(Sn, 0, 4, eS), slot(Sn, 1, 4, eS),
+                               slot(Sn, 2, 4, eS), quad(B, h.k, h.n, 1, 1), slot(Sn, 3, 4, eS)};
+            for (int j = 0; j < 7; ++j) mul(Ta[j], Sb[j], slot(Q, j, 7, eQ), h, level + 1, live);
+            op(S_POST, SW_CLASS_POST_ADD, bytes(live, h.m, h.n, 7, 4), {rng(Q, h.m, h.n, 7 * live)}, {rng(C, d.m, d.n, live)},
+               [&](hipStream_t st) { return launch_post_add(Q, live, h.m, h.n, C, st); });
         } else {
             // DFS step: the seven products one after the other (Section 3.4), written straight into the
-            // quadrants of C, with two temporaries X, Y per parent.  The additions are those of Appendix A
-            // in the printed association, so the result is bit-identical to the BFS form.
-            Mat X = ws_mat(take(live * e), h), Y = ws_mat(take(live * e), h);
-            const Mat A11 = quad(A, h, 0, 0), A12 = quad(A, h, 0, 1), A21 = quad(A, h, 1, 0), A22 = quad(A, h, 1, 1);
-            const Mat B11 = quad(B, h, 0, 0), B12 = quad(B, h, 0, 1), B21 = quad(B, h, 1, 0), B22 = quad(B, h, 1, 1);
-            const Mat C11 = quad(C, h, 0, 0), C12 = quad(C, h, 0, 1), C21 = quad(C, h, 1, 0), C22 = quad(C, h, 1, 1);
+            // quadrants of C, with two temporaries per parent: X holds the T operands and later the product Q0
+            // (two views of one buffer large enough for either), Y holds the S operands.  The additions are
+            // those of Appendix A in the printed association, so the result is bit-identical to the BFS form.
+            const int64_t eX = eT > eQ ? eT : eQ;
+            double* const xp = take(live * eX);
+            const Mat X{xp, ws_ld(h.k), eX, ws_ld(h.k) > h.k};      // as a T operand, h.m x h.k
+            const Mat XQ{xp, ws_ld(h.n), eX, ws_ld(h.n) > h.n};     // as the product Q0, h.m x h.n
+            const Mat Y = ws_mat(take(live * eS), h.k, h.n);
+            const Mat A11 = quad(A, h.m, h.k, 0, 0), A12 = quad(A, h.m, h.k, 0, 1), A21 = quad(A, h.m, h.k, 1, 0), A22 = quad(A, h.m, h.k, 1, 1);
+            const Mat B11 = quad(B, h.k, h.n, 0, 0), B12 = quad(B, h.k, h.n, 0, 1), B21 = quad(B, h.k, h.n, 1, 0), B22 = quad(B, h.k, h.n, 1, 1);
+            const Mat C11 = quad(C, h.m, h.n, 0, 0), C12 = quad(C, h.m, h.n, 0, 1), C21 = quad(C, h.m, h.n, 1, 0), C22 = quad(C, h.m, h.n, 1, 1);
             ew2(S_PRE, X, A11, A21, -1, Y, B22, B12, -1, live, h);     // T4 = A11 - A21, S4 = B22 - B12
             mul(X, Y, C21, h, level + 1, live);                        // C21 <- Q4
             ew2(S_PRE, X, A21, A22, +1, Y, B12, B11, -1, live, h);     // T2 = A21 + A22, S2 = B12 - B11
             mul(X, Y, C22, h, level + 1, live);                        // C22 <- Q2
             ew2(S_PRE, X, X, A11, -1, Y, B22, Y, -1, live, h);         // T3 = T2 - A11,  S3 = B22 - S2
             mul(X, Y, C12, h, level + 1, live);                        // C12 <- Q3
-            ew(S_PRE, X, A12, X, -1, live, h);                         // T5 = A12 - T3
+            ew(S_PRE, X, A12, X, -1, live, h.m, h.k);                  // T5 = A12 - T3
             mul(X, B22, C11, h, level + 1, live);                      // C11 <- Q5 = T5 * B22
-            mul(A11, B11, X, h, level + 1, live);                      // X   <- Q0 = A11 * B11
-            op(S_POST, SW_CLASS_DFS_ADD, bytes(live, h, 5, 3),
-               {rng(X, h, h, live), rng(C11, h, h, live), rng(C12, h, h, live), rng(C21, h, h, live), rng(C22, h, h, live)},
-               {rng(C12, h, h, live), rng(C21, h, h, live), rng(C22, h, h, live)},
-               [&](hipStream_t st) { return launch_dfs_post(X, C11, C12, C21, C22, live, h, st); });  // C12, C22 final; C21 = U2
-            ew(S_PRE, Y, Y, B21, -1, live, h);                         // S6 = S3 - B21
+            mul(A11, B11, XQ, h, level + 1, live);                     // X   <- Q0 = A11 * B11
+            op(S_POST, SW_CLASS_DFS_ADD, bytes(live, h.m, h.n, 5, 3),
+               {rng(XQ, h.m, h.n, live), rng(C11, h.m, h.n, live), rng(C12, h.m, h.n, live), rng(C21, h.m, h.n, live),
+                rng(C22, h.m, h.n, live)},
+               {rng(C12, h.m, h.n, live), rng(C21, h.m, h.n, live), rng(C22, h.m, h.n, live)},
+               [&](hipStream_t st) { return launch_dfs_post(XQ, C11, C12, C21, C22, live, h.m, h.n, st); });  // C12, C22 final; C21 = U2
+            ew(S_PRE, Y, Y, B21, -1, live, h.k, h.n);                  // S6 = S3 - B21
             mul(A22, Y, C11, h, level + 1, live);                      // C11 <- Q6 = A22 * S6
-            ew(S_POST, C21, C21, C11, -1, live, h);                    // C21 = U2 - Q6
+            ew(S_POST, C21, C21, C11, -1, live, h.m, h.n);             // C21 = U2 - Q6
             mul(A12, B21, C11, h, level + 1, live);                    // C11 <- Q1 = A12 * B21
-            ew(S_POST, C11, X, C11, +1, live, h);                      // C11 = Q0 + Q1
+            ew(S_POST, C11, XQ, C11, +1, live, h.m, h.n);              // C11 = Q0 + Q1
         }
         bg = was_bg;
         used = mark;
@@ -462,39 +486,43 @@ bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
     return a0 < b1 && b0 < a1;
 }
 
-int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
-                     int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
+int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                   int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
 {
+    const int64_t dmin = d.m < d.n ? (d.m < d.k ? d.m : d.k) : (d.n < d.k ? d.n : d.k);
+    const int64_t dmax = d.m > d.n ? (d.m > d.k ? d.m : d.k) : (d.n > d.k ? d.n : d.k);
     if (levels < 0) {
         // depth left open: the cost model's choice for this workspace, step order by the planner
-        if (n < 0 || n > 200000) { set_error("bad shape: n = %lld", (long long)n); return SW_EINVAL; }
-        levels = plan_levels(n, ws ? ws_bytes : 0);
+        if (dmin < 0 || dmax > 200000) { set_error("bad shape: %lld x %lld x %lld", (long long)d.m, (long long)d.n, (long long)d.k); return SW_EINVAL; }
+        levels = plan_levels(dmin, ws ? ws_bytes : 0);
         schedule = nullptr;
     }
-    int rc = check_shape(n, levels);
+    int rc = check_shape(dmin, levels);
+    if (rc == SW_OK) rc = check_shape(dmax, 0);
     if (rc != SW_OK) return rc;
-    if (n == 0) return SW_OK;
+    if (d.m == 0 || d.n == 0) return SW_OK;
+    if (d.k == 0) { set_error("empty inner dimension"); return SW_EINVAL; }
     if (!A || !B || !C) { set_error("NULL matrix pointer"); return SW_EINVAL; }
-    if (lda < n || ldb < n || ldc < n) { set_error("leading dimension smaller than n"); return SW_EINVAL; }
-    const int64_t spanA = (n - 1) * lda + n, spanB = (n - 1) * ldb + n, spanC = (n - 1) * ldc + n;
+    if (lda < d.k || ldb < d.n || ldc < d.n) { set_error("leading dimension smaller than the row length"); return SW_EINVAL; }
+    const int64_t spanA = (d.m - 1) * lda + d.k, spanB = (d.k - 1) * ldb + d.n, spanC = (d.m - 1) * ldc + d.n;
     if (overlaps(C, spanC, A, spanA) || overlaps(C, spanC, B, spanB)) {
         set_error("C overlaps A or B");
         return SW_EINVAL;
     }
     char chosen[SW_MAX_LEVELS + 1];
     if (!schedule || !*schedule) {
-        rc = plan(n, levels, ws ? ws_bytes : 0, chosen);
+        rc = plan(d, levels, ws ? ws_bytes : 0, chosen);
         if (rc != SW_OK) return rc;
         schedule = chosen;
     } else if (!schedule_ok(schedule, levels)) {
         set_error("schedule \"%s\" must be %d characters of B or D", schedule, levels);
         return SW_EINVAL;
     }
-    const int64_t need = total_need(n, levels, schedule);
+    const int64_t need = total_need(d, levels, schedule);
     if (need > 0) {
         if (!ws || ws_bytes < need) {
-            set_error("workspace of %lld bytes is too small: n = %lld, schedule %s needs %lld", (long long)(ws ? ws_bytes : 0),
-                      (long long)n, schedule, (long long)need);
+            set_error("workspace of %lld bytes is too small: %lld x %lld x %lld, schedule %s needs %lld", (long long)(ws ? ws_bytes : 0),
+                      (long long)d.m, (long long)d.n, (long long)d.k, schedule, (long long)need);
             return SW_ENOMEM;
         }
         if ((uintptr_t)ws & 255u) { set_error("workspace must be 256-byte aligned"); return SW_EINVAL; }
@@ -511,13 +539,14 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
     ex.sched = schedule;
     ex.levels = levels;
     const int64_t q = (int64_t)1 << levels;
-    const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
+    const bool peel = g_odd_mode == SW_ODD_PEEL && d.cube() && d.m % q != 0;
+    const Dims rec = peel ? Dims{d.m - d.m % q, d.m - d.m % q, d.m - d.m % q} : padded_dims(d, levels);
     {
         // spend what the workspace has beyond the minimum: first on a second set of the buffers next to the
         // leaves (so that additions and leaf products of consecutive launches overlap), then on the rich form
         // of the deepest DFS steps
-        const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
-        choose_options(nrec, levels, schedule, ws_bytes - fixed, g_overlap != 0, &ex.rich, &ex.dbl);
+        const int64_t fixed = need - ws_need_bytes(rec, schedule, 1);
+        choose_options(rec, levels, schedule, ws_bytes - fixed, g_overlap != 0, &ex.rich, &ex.dbl);
     }
     ex.prof = profiler();
     // with BFS steps only the kernels form one chain: nothing could overlap, so one stream it is
@@ -526,13 +555,12 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
     ex.cap_fixed = g_overlap;
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
-    const int64_t r = n % q;
-    if (r != 0 && g_odd_mode == SW_ODD_PEEL) {
-        // Peeling (Section 3.1 names it beside padding): the leading n0 x n0 blocks, n0 the previous multiple
-        // of 2^levels, go through the recursion in place; the r < 2^levels peeled rows and columns are
-        // finished by three thin classical products on the same MFMA kernel.
-        const int64_t n0 = n - r;
-        ex.mul(a, b, c, n0, 0, 1);                                   // C11  = A11 * B11
+    if (peel) {
+        // Peeling (Section 3.1 names it beside padding), square products only: the leading n0 x n0 blocks, n0
+        // the previous multiple of 2^levels, go through the recursion in place; the r < 2^levels peeled rows
+        // and columns are finished by three thin classical products on the same MFMA kernel.
+        const int64_t n = d.m, r = n % q, n0 = n - r;
+        ex.mul(a, b, c, rec, 0, 1);                                  // C11  = A11 * B11
         const Mat a12{a.p + n0, lda, 0}, b21{b.p + n0 * ldb, ldb, 0};
         const Mat bright{b.p + n0, ldb, 0}, c12{c.p + n0, ldc, 0};
         const Mat abot{a.p + n0 * lda, lda, 0}, cbot{c.p + n0 * ldc, ldc, 0};
@@ -544,26 +572,27 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
                   return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
               });
     } else {
-        const int64_t np = padded_n(n, levels);
-        if (np != n) {
-            // zero-pad into workspace copies of the next multiple of 2^levels (Section 3.1)
-            const int64_t ld = ws_ld(np), e = ws_mat_elems(np);
-            a = Mat{ex.take(e), ld, 0, ld > np};
-            b = Mat{ex.take(e), ld, 0, ld > np};
-            c = Mat{ex.take(e), ld, 0, ld > np};
+        const Dims p = rec;
+        const bool padded = p.m != d.m || p.n != d.n || p.k != d.k;
+        if (padded) {
+            // zero-pad into workspace copies of the next multiples of 2^levels (Section 3.1)
+            a = ws_mat(ex.take(ws_mat_elems(p.m, p.k)), p.m, p.k);
+            b = ws_mat(ex.take(ws_mat_elems(p.k, p.n)), p.k, p.n);
+            c = ws_mat(ex.take(ws_mat_elems(p.m, p.n)), p.m, p.n);
+            a.stride = b.stride = c.stride = 0;
             const Mat ua{const_cast<double*>(A), lda, 0}, ub{const_cast<double*>(B), ldb, 0};
-            ex.op(S_PRE, SW_CLASS_PAD, 8.0 * (2.0 * n * n + 2.0 * np * np), {rng(ua, n, n), rng(ub, n, n)},
-                  {rng(a, np, np), rng(b, np, np)}, [&](hipStream_t st) {
-                      hipError_t e1 = launch_pad_copy(A, lda, n, n, a.p, ld, np, np, st);
-                      hipError_t e2 = launch_pad_copy(B, ldb, n, n, b.p, ld, np, np, st);
+            ex.op(S_PRE, SW_CLASS_PAD, 8.0 * ((double)d.m * d.k + (double)d.k * d.n + (double)p.m * p.k + (double)p.k * p.n),
+                  {rng(ua, d.m, d.k), rng(ub, d.k, d.n)}, {rng(a, p.m, p.k), rng(b, p.k, p.n)}, [&](hipStream_t st) {
+                      hipError_t e1 = launch_pad_copy(A, lda, d.m, d.k, a.p, a.ld, p.m, p.k, st);
+                      hipError_t e2 = launch_pad_copy(B, ldb, d.k, d.n, b.p, b.ld, p.k, p.n, st);
                       return e1 != hipSuccess ? e1 : e2;
                   });
         }
-        ex.mul(a, b, c, np, 0, 1);
-        if (np != n) {
+        ex.mul(a, b, c, p, 0, 1);
+        if (padded) {
             const Mat uc{C, ldc, 0};
-            ex.op(S_POST, SW_CLASS_PAD, 8.0 * 2.0 * n * n, {rng(c, np, np)}, {rng(uc, n, n)},
-                  [&](hipStream_t st) { return launch_pad_copy(c.p, c.ld, np, np, C, ldc, n, n, st); });
+            ex.op(S_POST, SW_CLASS_PAD, 8.0 * 2.0 * (double)d.m * d.n, {rng(c, p.m, p.n)}, {rng(uc, d.m, d.n)},
+                  [&](hipStream_t st) { return launch_pad_copy(c.p, c.ld, p.m, p.n, C, ldc, d.m, d.n, st); });
         }
     }
     ex.sc.finish();
@@ -571,6 +600,12 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
     ex.note(ex.sc.err);
     if (ex.err != hipSuccess) return hip_fail(ex.err, "kernel launch");
     return SW_OK;
+}
+
+int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+              int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
+{
+    return gemm_rect_impl(Dims{n, n, n}, A, lda, B, ldb, C, ldc, levels, schedule, ws, ws_bytes, stream);
 }
 
 }  // namespace sw

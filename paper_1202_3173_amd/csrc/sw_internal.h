@@ -22,8 +22,16 @@ inline int64_t ws_ld(int64_t h)
     return ld;
 }
 
-// Elements reserved for one h x h workspace matrix (a multiple of 32 doubles = 256 bytes).
-inline int64_t ws_mat_elems(int64_t h) { return (ws_ld(h) * h + 31) / 32 * 32; }
+// Shape of one product: C (m x n) = A (m x k) * B (k x n).  The recursion halves all three at every step.
+struct Dims {
+    int64_t m, n, k;
+    Dims half() const { return Dims{m / 2, n / 2, k / 2}; }
+    bool cube() const { return m == n && n == k; }
+};
+
+// Elements reserved for one rows x cols workspace matrix (a multiple of 32 doubles = 256 bytes).
+inline int64_t ws_mat_elems(int64_t rows, int64_t cols) { return (ws_ld(cols) * rows + 31) / 32 * 32; }
+inline int64_t ws_mat_elems(int64_t h) { return ws_mat_elems(h, h); }
 
 // A run of consecutive BFS steps is executed in fused pairs, deepest pairs first: with an even number of B
 // ahead the next two steps share one pass and the operands of the level between them are never stored.
@@ -34,48 +42,59 @@ inline bool fuse_two_bfs(const char* sched)
     return run >= 2 && run % 2 == 0;
 }
 
-// Bytes of workspace the executor takes for an np x np problem (np a multiple of 2^levels) whose remaining
-// step order is `sched`, entered with `live` parents.  BFS step: T, S, Q for all seven children of every
-// parent (Section 3.3.1), or for all 49 grandchildren when two BFS steps are fused; DFS step: two
-// temporaries per parent, because products are written straight into the parent's C quadrants (the footnote
-// of Section 3.3.1 allows a few temporaries).
+// Bytes of workspace the executor takes for a problem of shape d (every extent a multiple of 2^levels) whose
+// remaining step order is `sched`, entered with `live` parents.  With T (m/2 x k/2), S (k/2 x n/2) and
+// Q (m/2 x n/2) the operands and the product of one child:  BFS step: T, S, Q for all seven children of
+// every parent (Section 3.3.1), or for all 49 grandchildren when two BFS steps are fused; DFS step: two
+// temporaries per parent -- one that holds a T and later a Q, one that holds an S -- because products are
+// written straight into the parent's C quadrants (the footnote of Section 3.3.1 allows a few temporaries).
 //
 // rich: bit i set = the DFS step at level `level + i` keeps its four non-trivial T, four S and seven Q (15
 // buffers per parent, the storage of a BFS step without the plain copies) while still solving the seven
 // subproblems in sequence; its additions are then the one-pass BFS kernels.  0 = the minimum.
 // dbl: the buffers of the step whose children are the leaves exist twice (consecutive leaf launches then
 // alternate between the two sets, so the additions of one launch overlap the products of another).
-inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live, uint32_t rich = 0, bool dbl = false)
+inline int64_t ws_need_bytes(Dims d, const char* sched, int64_t live, uint32_t rich = 0, bool dbl = false)
 {
     if (*sched == '\0') return 0;
-    const int64_t h = n / 2;
-    const int64_t e = ws_mat_elems(h) * (int64_t)sizeof(double);
+    const Dims h = d.half();
+    const int64_t W = (int64_t)sizeof(double);
+    const int64_t eT = ws_mat_elems(h.m, h.k) * W, eS = ws_mat_elems(h.k, h.n) * W, eQ = ws_mat_elems(h.m, h.n) * W;
     if (fuse_two_bfs(sched)) {
-        const int64_t e4 = ws_mat_elems(h / 2) * (int64_t)sizeof(double);
+        const Dims q = h.half();
+        const int64_t e4 = (ws_mat_elems(q.m, q.k) + ws_mat_elems(q.k, q.n) + ws_mat_elems(q.m, q.n)) * W;
         const int copies = (dbl && sched[2] == '\0') ? 2 : 1;
-        return copies * 3 * 49 * live * e4 + ws_need_bytes(h / 2, sched + 2, 49 * live, rich >> 2, dbl);
+        return copies * 49 * live * e4 + ws_need_bytes(q, sched + 2, 49 * live, rich >> 2, dbl);
     }
     if (*sched == 'B') {
         const int copies = (dbl && sched[1] == '\0') ? 2 : 1;
-        return copies * 21 * live * e + ws_need_bytes(h, sched + 1, 7 * live, rich >> 1, dbl);
+        return copies * 7 * live * (eT + eS + eQ) + ws_need_bytes(h, sched + 1, 7 * live, rich >> 1, dbl);
     }
-    return ((rich & 1u) ? 15 : 2) * live * e + ws_need_bytes(h, sched + 1, live, rich >> 1, dbl);
+    const int64_t here = (rich & 1u) ? 4 * eT + 4 * eS + 7 * eQ : (eT > eQ ? eT : eQ) + eS;
+    return live * here + ws_need_bytes(h, sched + 1, live, rich >> 1, dbl);
+}
+inline int64_t ws_need_bytes(int64_t n, const char* sched, int64_t live, uint32_t rich = 0, bool dbl = false)
+{
+    return ws_need_bytes(Dims{n, n, n}, sched, live, rich, dbl);
 }
 
 // What to spend a workspace of `budget` bytes on beyond the minimum: first the second set of leaf-side
 // buffers (only useful when the leaves are reached more than once, i.e. below some DFS step, and when
 // additions and products run on separate streams), then the rich form of DFS steps, deepest first.
-inline void choose_options(int64_t n, int levels, const char* sched, int64_t budget, bool overlap, uint32_t* rich,
-                           bool* dbl)
+inline void choose_options(Dims d, int levels, const char* sched, int64_t budget, bool overlap, uint32_t* rich, bool* dbl)
 {
     *rich = 0;
     *dbl = false;
     bool any_dfs = false;
     for (int i = 0; i < levels; ++i) any_dfs = any_dfs || sched[i] == 'D';
-    if (overlap && any_dfs && levels > 0 && sched[levels - 1] == 'B' && ws_need_bytes(n, sched, 1, 0, true) <= budget)
+    if (overlap && any_dfs && levels > 0 && sched[levels - 1] == 'B' && ws_need_bytes(d, sched, 1, 0, true) <= budget)
         *dbl = true;
     for (int i = levels - 1; i >= 0; --i)
-        if (sched[i] == 'D' && ws_need_bytes(n, sched, 1, *rich | (1u << i), *dbl) <= budget) *rich |= 1u << i;
+        if (sched[i] == 'D' && ws_need_bytes(d, sched, 1, *rich | (1u << i), *dbl) <= budget) *rich |= 1u << i;
+}
+inline void choose_options(int64_t n, int levels, const char* sched, int64_t budget, bool overlap, uint32_t* rich, bool* dbl)
+{
+    choose_options(Dims{n, n, n}, levels, sched, budget, overlap, rich, dbl);
 }
 
 inline int64_t padded_n(int64_t n, int levels)
@@ -97,14 +116,20 @@ bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn);   // el
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream);     // what sw_set_workspace / sw_set_stream left
 
 // workspace bytes of the Strassen-Winograd product for this step order (with the padded copies, if any)
-int64_t total_need(int64_t n, int levels, const char* sched);
+int64_t total_need(Dims d, int levels, const char* sched);
+inline int64_t total_need(int64_t n, int levels, const char* sched) { return total_need(Dims{n, n, n}, levels, sched); }
 // the planner: most BFS steps that fit `budget`, then least memory; writes levels + 1 characters
-int plan(int64_t n, int levels, int64_t budget, char* out);
+int plan(Dims d, int levels, int64_t budget, char* out);
+inline int plan(int64_t n, int levels, int64_t budget, char* out) { return plan(Dims{n, n, n}, levels, budget, out); }
 // the depth with the least modelled time among those some step order fits into `budget` bytes (0 < n <= 200000)
 int plan_levels(int64_t n, int64_t budget);
 // the Strassen-Winograd product itself with explicit leading dimensions, workspace and stream (what sw_gemm_ex calls)
 int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
               int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream);
+// the same recursion on a rectangular product C (m x n) = A (m x k) * B (k x n); extents that 2^levels does
+// not divide are zero-padded into workspace copies
+int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                   int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream);
 
 // ---- profiling record (sw_profile_enable / sw_profile_read) ---------------------------------------------------
 
@@ -124,13 +149,15 @@ struct Mat {
 
 // Quadrant (i, j) of a batch of 2h x 2h matrices.  Behind a row of a left or top quadrant lies the right
 // quadrant or the next row; only the bottom-right quadrant inherits the question from its parent.
-inline Mat quad(const Mat& m, int64_t h, int i, int j)
+inline Mat quad(const Mat& m, int64_t hr, int64_t hc, int i, int j)
 {
-    return Mat{m.p + i * h * m.ld + j * h, m.ld, m.stride, m.padded || !(i == 1 && j == 1)};
+    return Mat{m.p + i * hr * m.ld + j * hc, m.ld, m.stride, m.padded || !(i == 1 && j == 1)};
 }
+inline Mat quad(const Mat& m, int64_t h, int i, int j) { return quad(m, h, h, i, j); }
 
-// A batch of h x h matrices in the workspace (pitch ws_ld(h), slot ws_mat_elems(h)).
-inline Mat ws_mat(double* p, int64_t h) { return Mat{p, ws_ld(h), ws_mat_elems(h), ws_ld(h) > h}; }
+// A batch of rows x cols matrices in the workspace (pitch ws_ld(cols), slot ws_mat_elems(rows, cols)).
+inline Mat ws_mat(double* p, int64_t rows, int64_t cols) { return Mat{p, ws_ld(cols), ws_mat_elems(rows, cols), ws_ld(cols) > cols}; }
+inline Mat ws_mat(double* p, int64_t h) { return ws_mat(p, h, h); }
 
 // ---- kernel launchers (each validates nothing: callers pass consistent shapes) --------------------------------
 
