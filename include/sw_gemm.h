@@ -53,6 +53,16 @@ int sw_gemm(int64_t n, const double* A, const double* B, double* C, int levels, 
 int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* The same recursion on a rectangular product: C (M x N) = A (M x K) * B (K x N), row-major with leading
+ * dimensions lda >= K, ldb >= N, ldc >= N.  Every step halves all three extents: the operands T are
+ * M/2 x K/2, S are K/2 x N/2, the products Q are M/2 x N/2 (Appendix A holds for any conformal 2 x 2
+ * blocking).  Extents that 2^levels does not divide are zero-padded into workspace copies (peeling is for
+ * square products only).  Otherwise as sw_gemm_ex; workspace_bytes >= sw_plan_memory_rect.
+ * Errors as sw_gemm_ex; SW_EINVAL also when 2^levels exceeds the smallest extent or K == 0 with M, N > 0. */
+int sw_gemm_rect(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
+                 int64_t ldc, int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);
+int64_t sw_plan_memory_rect(int64_t M, int64_t N, int64_t K, int levels, const char* schedule);
+
 /* The product with diagonal scaling (Section 6.1): D1 C D3 = (D1 A D2)(D2^-1 B D3) with D1, D2, D3 diagonal
  * powers of two (scaling and unscaling are exact).  scaling: SW_SCALE_OUTSIDE (D1, D3: every row of A and
  * column of B gets a largest entry in [1, 2); the error of entry (i, j) then relates to ||A(i,:)|| ||B(:,j)||

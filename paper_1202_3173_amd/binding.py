@@ -17,7 +17,7 @@ EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
            "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
-           "sw_plan_levels", "sw_model_seconds")
+           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect")
 
 
 class SwError(RuntimeError):
@@ -44,6 +44,8 @@ def lib():
         "sw_plan_memory": (i64, [i64, ci, cp]),
         "sw_gemm_scaled": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
+        "sw_gemm_rect": (ci, [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
+        "sw_plan_memory_rect": (i64, [i64, i64, i64, ci, cp]),
         "sw_dgemm": (ci, [ci, ci, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, cp]),
         "sw_plan_memory_dgemm": (i64, [ci, ci, i64, i64, i64, ci, cp]),
         "sw_plan_levels": (ci, [i64, i64]),
@@ -186,6 +188,20 @@ def sw_gemm_scaled(n, A, B, C, levels, schedule, scaling):
 
 def sw_plan_memory_scaled(n, levels, schedule=None):
     return _check(lib().sw_plan_memory_scaled(n, levels, _sched(schedule)))
+
+
+def sw_gemm_rect(M, N, K, A, lda, B, ldb, C, ldc, levels, schedule, workspace, stream_handle=None):
+    """C (M x N) = A (M x K) @ B (K x N) by the same recursion on rectangular operands."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+    ws_ptr = None if workspace is None else _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = _stream(C) if stream_handle is None else ctypes.c_void_p(stream_handle)
+    return _check(lib().sw_gemm_rect(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, levels, _sched(schedule), ws_ptr, ws_bytes, st))
+
+
+def sw_plan_memory_rect(M, N, K, levels, schedule=None):
+    return _check(lib().sw_plan_memory_rect(M, N, K, levels, _sched(schedule)))
 
 
 def sw_dgemm(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, levels, schedule=None):

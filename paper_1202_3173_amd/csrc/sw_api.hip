@@ -628,6 +628,29 @@ int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t
     return gemm_impl(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+int sw_gemm_rect(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
+                 int64_t ldc, int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream)
+{
+    if (workspace_bytes < 0) { set_error("negative workspace size"); return SW_EINVAL; }
+    if (M < 0 || N < 0 || K < 0) { set_error("negative dimension"); return SW_EINVAL; }
+    return gemm_rect_impl(Dims{M, N, K}, A, lda, B, ldb, C, ldc, levels, schedule, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int64_t sw_plan_memory_rect(int64_t M, int64_t N, int64_t K, int levels, const char* schedule)
+{
+    if (M < 0 || N < 0 || K < 0) { set_error("negative dimension"); return SW_EINVAL; }
+    const int64_t dmin = M < N ? (M < K ? M : K) : (N < K ? N : K), dmax = M > N ? (M > K ? M : K) : (N > K ? N : K);
+    int rc = check_shape(dmin, levels);
+    if (rc == SW_OK) rc = check_shape(dmax, 0);
+    if (rc != SW_OK) return rc;
+    std::string s = (schedule && *schedule) ? std::string(schedule) : std::string((size_t)levels, 'D');
+    if (!schedule_ok(s.c_str(), levels)) {
+        set_error("schedule \"%s\" must be %d characters of B or D", s.c_str(), levels);
+        return SW_EINVAL;
+    }
+    return total_need(Dims{M, N, K}, levels, s.c_str());
+}
+
 // ---- diagonal scaling around the product (Section 6.1) ------------------------------------------------------
 
 static int64_t scaled_extra_bytes(int64_t n)

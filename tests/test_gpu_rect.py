@@ -1,0 +1,118 @@
+"""The recursion on rectangular products (sw_gemm_rect) on the GPU.
+
+Appendix A's step holds for any conformal 2 x 2 blocking, so nothing new is computed: integer-valued operands
+must give the exact product bit for bit for every shape, depth, step order, executor and workspace size; real
+operands stay inside 1e-10 * K * max|A| * max|B| of the general-product oracle; a cube must give the same bits as
+sw_gemm_ex."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_1202_3173_amd import binding as sw
+from paper_1202_3173_amd import inputs
+
+sys.path.insert(0, os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle"))
+import sw_dgemm as oracle_dgemm  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def rect(rows, cols, seed, which, dist):
+    n = max(rows, cols)
+    return np.ascontiguousarray(inputs.matrix(n, seed, which, dist)[:rows, :cols])
+
+
+def run(A, B, levels, schedule, roomy=False, pads=(0, 0, 0)):
+    M, K = A.shape
+    N = B.shape[1]
+    dA = torch.full((M, K + pads[0]), float("nan"), dtype=torch.float64, device=DEV)
+    dB = torch.full((K, N + pads[1]), float("nan"), dtype=torch.float64, device=DEV)
+    dC = torch.full((M, N + pads[2]), float("nan"), dtype=torch.float64, device=DEV)
+    dA[:, :K] = torch.from_numpy(A).to(DEV)
+    dB[:, :N] = torch.from_numpy(B).to(DEV)
+    need = sw.sw_plan_memory_rect(M, N, K, levels, schedule)
+    ws = torch.empty(max(need * (4 if roomy else 1) + (1 << 20 if roomy else 0), 256), dtype=torch.uint8, device=DEV)
+    sw.sw_gemm_rect(M, N, K, dA, K + pads[0], dB, N + pads[1], dC, N + pads[2], levels, schedule, ws)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    if pads[2]:
+        assert np.all(np.isnan(got[:, N:])), "wrote into the padding of C"
+    return got[:, :N]
+
+
+SHAPES = [(64, 32, 96, 2, ["BB", "DD", "BD", "DB"]), (256, 512, 128, 3, ["BBB", "DBD", "DDD"]),
+          (1000, 200, 600, 2, ["BB", "DB", "DD"]),          # leaves 250 x 50 x 150
+          (130, 70, 90, 1, ["B", "D"]),                      # odd halves: 8-byte paths
+          (333, 200, 111, 2, ["BD", "DB"]),                  # padded to 336 x 200 x 112
+          (96, 2048, 64, 4, ["BBBB", "DBBB", "DDBB"]),       # leaves 6 x 128 x 4
+          (1536, 768, 1024, 3, ["DBB", "DDB"])]
+
+
+@pytest.mark.parametrize("M,N,K,levels,schedules", SHAPES)
+def test_integer_products_exact_for_every_order(M, N, K, levels, schedules):
+    A = rect(M, K, 60 + M, 0, "integer")
+    B = rect(K, N, 60 + M, 1, "integer")
+    exact = A @ B          # small integers: every partial sum is exact in fp64
+    for s in schedules:
+        for roomy in (False, True):
+            assert np.array_equal(run(A, B, levels, s, roomy, pads=(2, 0, 3)), exact), (s, roomy)
+
+
+@pytest.mark.parametrize("M,N,K,levels,schedule", [(96, 40, 64, 2, "BD"), (320, 500, 200, 2, "DB"), (500, 120, 260, 2, "BB")])
+def test_real_products_within_tolerance_and_order_independent(M, N, K, levels, schedule):
+    A = rect(M, K, 9, 0, "uniform")
+    B = rect(K, N, 9, 1, "rowscaled")
+    ref = oracle_dgemm.dgemm(False, False, 1.0, A, B, 0.0, np.zeros((M, N)))
+    got = run(A, B, levels, schedule)
+    assert np.max(np.abs(got - ref)) <= 1e-10 * K * np.max(np.abs(A)) * np.max(np.abs(B))
+    other = run(A, B, levels, "D" * levels, roomy=True)
+    assert np.array_equal(got, other), "result depends on the step order"
+
+
+def test_cube_gives_the_bits_of_the_square_entry_point():
+    n, levels, schedule = 384, 3, "DBB"
+    A = rect(n, n, 4, 0, "uniform")
+    B = rect(n, n, 4, 1, "uniform")
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    C = torch.empty((n, n), dtype=torch.float64, device=DEV)
+    ws = torch.empty(sw.sw_plan_memory(n, levels, schedule), dtype=torch.uint8, device=DEV)
+    sw.sw_gemm_ex(n, dA, n, dB, n, C, n, levels, schedule, ws)
+    torch.cuda.synchronize()
+    assert sw.sw_plan_memory_rect(n, n, n, levels, schedule) == sw.sw_plan_memory(n, levels, schedule)
+    assert np.array_equal(run(A, B, levels, schedule), C.cpu().numpy())
+
+
+def test_seeded_sweep_is_exact():
+    rng = np.random.default_rng(31337)
+    try:
+        for case in range(40):
+            levels = int(rng.integers(0, 4))
+            lo = max(1 << levels, 1)
+            M, N, K = (int(rng.integers(lo, 450)) for _ in range(3))
+            schedule = "".join(rng.choice(["B", "D"]) for _ in range(levels))
+            sw.sw_set_overlap(bool(rng.integers(0, 2)))
+            A = rect(M, K, 7000 + case, 0, "integer")
+            B = rect(K, N, 7000 + case, 1, "integer")
+            pads = tuple(int(x) for x in rng.integers(0, 3, size=3))
+            got = run(A, B, levels, schedule, roomy=bool(rng.integers(0, 2)), pads=pads)
+            assert np.array_equal(got, A @ B), (case, M, N, K, levels, schedule, pads)
+    finally:
+        sw.sw_set_overlap(True)
+
+
+def test_errors():
+    t = torch.zeros((64, 64), dtype=torch.float64, device=DEV)
+    c = torch.zeros((64, 64), dtype=torch.float64, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    for args, code in [((64, 64, 64, t, 63, t, 64, c, 64, 1, "B", ws), -1),      # lda < K
+                       ((64, 64, 2, t, 64, t, 64, c, 64, 2, "BB", ws), -1),      # 2^levels > K
+                       ((64, 64, 64, t, 64, t, 64, t, 64, 1, "B", ws), -1),      # C is A
+                       ((64, 64, 64, t, 64, t, 64, c, 64, 1, "B", None), -2)]:   # no workspace
+        with pytest.raises(sw.SwError) as e:
+            sw.sw_gemm_rect(*args)
+        assert e.value.code == code

@@ -224,3 +224,22 @@ def test_plan_levels_and_dgemm_memory():
     assert sw.sw_plan_memory_dgemm(1, 1, M, N, K, L, "DBB") - inner == 3 * one
     with pytest.raises(sw.SwError):
         sw.sw_plan_memory_dgemm(0, 0, 64, 64, 3, 2, "BB")
+
+
+def test_rectangular_memory_formula():
+    def elems(rows, cols):     # the documented workspace rule: pitch a multiple of 16, never of 256; slots of 32
+        ld = (cols + 15) // 16 * 16
+        ld += 16 if ld >= 256 and ld % 256 == 0 else 0
+        return (ld * rows + 31) // 32 * 32
+    M, N, K = 1024, 512, 2048
+    # one BFS step: seven T (M/2 x K/2), seven S (K/2 x N/2), seven Q (M/2 x N/2)
+    assert sw.sw_plan_memory_rect(M, N, K, 1, "B") == 7 * 8 * (elems(512, 1024) + elems(1024, 256) + elems(512, 256))
+    # one DFS step: a temporary that holds a T or a Q, and one for an S
+    assert sw.sw_plan_memory_rect(M, N, K, 1, "D") == 8 * (max(elems(512, 1024), elems(512, 256)) + elems(1024, 256))
+    # a cube is the square product
+    assert sw.sw_plan_memory_rect(4096, 4096, 4096, 3, "DBB") == sw.sw_plan_memory(4096, 3, "DBB")
+    # padding: three copies at the padded extents
+    base = sw.sw_plan_memory_rect(104, 72, 40, 3, "DDD")
+    assert sw.sw_plan_memory_rect(100, 70, 33, 3, "DDD") == base + 8 * (elems(104, 40) + elems(40, 72) + elems(104, 72))
+    with pytest.raises(sw.SwError):
+        sw.sw_plan_memory_rect(64, 64, 3, 2, "BB")
