@@ -103,16 +103,19 @@ double sw_flop_count_bilinear(int64_t n, int levels, int scheme);
 
 /* C <- alpha * op(A) * op(B) + beta * C, the operation the fast algorithm replaces (Section 1), on row-major
  * rectangular operands: op(A) is M x K, op(B) is K x N, C is M x N; transa / transb != 0 take the transpose,
- * the stored matrix then being K x M (lda >= M) or N x K (ldb >= K).  The operands are cut into square
- * s x s blocks; every block product runs through the Strassen-Winograd recursion (`levels` steps, `schedule`
- * as for sw_gemm on an s x s problem) and the rows, columns and inner indices left over (fewer than s each)
- * through the classical MFMA product.  s is floor(min(M, N, K) / j) rounded down to a multiple of 2^levels
- * for the j in 1 .. 8 whose modelled time is least among those the workspace holds (one block recurses
- * deepest, more blocks leave less to the classical remainders).  levels < 0: the depth is chosen with s by
- * the same model (sw_plan_levels) for the workspace that is set (schedule is then ignored).  beta == 0: C is not read; alpha == 0 or K == 0: A and B
- * are not read.  alpha, beta are passed by value.  Uses the workspace and stream of sw_set_workspace /
- * sw_set_stream; a workspace of sw_plan_memory_dgemm bytes (j = 1: one s x s temporary, one more per
- * transposed operand, and the recursion's own) always suffices.  C must not overlap A or B.
+ * the stored matrix then being K x M (lda >= M) or N x K (ldb >= K).  The product is cut into blocks of
+ * s_m x s_n x s_k: M, N and K each into 1 .. 4 equal parts, rounded down to a multiple of 2^levels.  Every
+ * block product runs through the Strassen-Winograd recursion on rectangular operands (sw_gemm_rect: `levels`
+ * steps, `schedule` as for that call) into a temporary and is folded into C in one pass (or is written
+ * straight into C when alpha = 1, beta = 0 and K is one part); a transposed operand is transposed block by
+ * block into a temporary; the rows, columns and inner indices left over (fewer than 4 * 2^levels each) go
+ * through the classical MFMA product.  Among the block shapes whose need the workspace holds, the one with
+ * the least modelled time is taken.  levels < 0: the depth is chosen with the block shape by the same model
+ * (schedule is then ignored).  beta == 0: C is not read; alpha == 0 or K == 0: A and B are not read.  alpha,
+ * beta are passed by value.  Uses the workspace and stream of sw_set_workspace / sw_set_stream; a workspace
+ * of sw_plan_memory_dgemm bytes (the whole product as one block: a temporary for C, one more per transposed
+ * operand, and the recursion's own) always suffices, smaller ones work with smaller blocks.  C must not
+ * overlap A or B.
  * Errors: SW_EINVAL (negative or > 200000 dimension, 2^levels > min(M, N, K), short leading dimension, NULL
  * pointer, overlap, bad schedule), SW_ENOMEM, SW_EHIP. */
 int sw_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double* A, int64_t lda,

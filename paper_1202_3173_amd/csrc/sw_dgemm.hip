@@ -75,96 +75,109 @@ hipError_t launch_axpby(double* C, int64_t ldc, const double* P, int64_t ldp, in
 }
 
 // ---- cost model for the recursion depth -----------------------------------------------------------------------
-// Leaf products: 7^L classical products of size m = n / 2^L, launched 7^(BFS steps) at a time, at the rate the
-// MFMA kernel reaches on m x m (a measured table), times the fill of its 128 x 128 tiles, times the fill of
-// the 512 workgroup slots by the tiles of one launch.
-// Additions: per parent and step, in half-size matrices moved through HBM: 33 for a BFS step, 48.75 for
-// two fused BFS steps (in units of the upper one), 38 for a DFS step with two temporaries, 27 for one that
-// keeps its operands; at 5.2 TB/s, plus a few microseconds per launch.  The constants are fitted to
-// measurements on one MI355X at n = 2048 .. 94080.
-double leaf_rate(double m, double batch)
+// Leaf products: 7^L classical products of the shape 1/2^L of the problem's, launched 7^(BFS steps) at a time,
+// at the rate the MFMA kernel reaches for that inner extent (a measured table), times the fill of its
+// 128 x 128 tiles, times the fill of the 512 workgroup slots by the tiles of one launch.
+// Additions: elements moved per parent and step (see step_elems; for a cube 33, 48.75, 38 or 27 half-size
+// matrices) at 5.2 TB/s, plus a few microseconds per launch.  The constants are fitted to measurements on one
+// MI355X at n = 2048 .. 94080.
+// by inner extent k of the leaf (the length of the K loop decides how much prologue and epilogue weigh)
+double table_rate(double k)
 {
-    // rate on full tiles with all workgroup slots busy, TFLOP/s, by leaf size (measured; between the points
-    // linear in log2 m): short inner loops leave prologue and epilogue of every tile exposed
+    // rate on full tiles with all workgroup slots busy, TFLOP/s, by leaf size (measured on square leaves;
+    // between the points linear in log2): short inner loops leave prologue and epilogue of every tile exposed
     static const double size[] = {64, 128, 256, 512, 1024, 2048, 4096, 8192};
     static const double rate[] = {12, 27, 47, 61, 72, 74, 75.3, 76.4};
-    double r = rate[7];
-    if (m <= size[0]) r = rate[0] * m / size[0];
-    else
-        for (int i = 1; i < 8; ++i)
-            if (m <= size[i]) {
-                const double f = (log2(m) - log2(size[i - 1])) / (log2(size[i]) - log2(size[i - 1]));
-                r = rate[i - 1] + f * (rate[i] - rate[i - 1]);
-                break;
-            }
-    const double edge = ceil(m / 128.0);
-    const double fill = (m / (edge * 128.0)) * (m / (edge * 128.0));          // tiles that hang over the edge
-    const double tiles = batch * edge * edge;
+    if (k <= size[0]) return rate[0] * k / size[0];
+    for (int i = 1; i < 8; ++i)
+        if (k <= size[i]) {
+            const double f = (log2(k) - log2(size[i - 1])) / (log2(size[i]) - log2(size[i - 1]));
+            return rate[i - 1] + f * (rate[i] - rate[i - 1]);
+        }
+    return rate[7];
+}
+
+double leaf_rate(double m, double n, double k, double batch)
+{
+    const double em = ceil(m / 128.0), en = ceil(n / 128.0);
+    const double fill = (m / (em * 128.0)) * (n / (en * 128.0));             // tiles that hang over the edge
+    const double tiles = batch * em * en;
     // 512 workgroup slots (two per CU) are filled in rounds; a last round of at most 256 tiles has every CU
     // to one workgroup, which then runs at 0.89 of the rate of two and finishes in 0.56 of a round
     const double full = floor(tiles / 512.0), rest = tiles - 512.0 * full;
     const double rounds = full + (rest == 0.0 ? 0.0 : (rest <= 256.0 ? 0.56 : 1.0));
-    return r * 1e12 * fill * (tiles / 512.0) / rounds;
+    return table_rate(k) * 1e12 * fill * (tiles / 512.0) / rounds;
 }
 
-double modelled_seconds(int64_t n, int levels, const char* order, uint32_t rich)
+// elements moved per parent by the additions of one step on children of shape h (T: h.m x h.k, S: h.k x h.n,
+// Q: h.m x h.n): a BFS step reads 4 and writes 7 on each operand side and reads 7, writes 4 for C; two fused
+// BFS steps 16 and 49 of the quarter blocks; a DFS step with two temporaries 12, 12 and 14; one that keeps
+// its operands 8, 8 and 11
+double step_elems(Dims h, double a, double b, double c)
+{
+    return a * (double)h.m * (double)h.k + b * (double)h.k * (double)h.n + c * (double)h.m * (double)h.n;
+}
+
+double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich)
 {
     constexpr double HBM = 5.2e12, LAUNCH = 6e-6;
-    const int64_t np = padded_n(n, levels);
-    const double m = (double)(np >> levels);
-    double t = 0.0, parents = 1.0, launches = 1.0, h = (double)np;   // `launches` subtrees in sequence, `parents` in each
+    const Dims p{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)};
+    double t = 0.0, parents = 1.0, launches = 1.0;   // `launches` subtrees in sequence, `parents` in each
+    Dims h = p;
     for (int i = 0; i < levels;) {
-        h /= 2;
-        const double unit = 8.0 * h * h;
+        h = h.half();
         if (fuse_two_bfs(order + i)) {
-            t += launches * (parents * 48.75 * unit / HBM + 3 * LAUNCH);
+            h = h.half();
+            t += launches * (parents * 8.0 * step_elems(h, 65, 65, 65) / HBM + 3 * LAUNCH);
             parents *= 49.0;
-            h /= 2;
             i += 2;
         } else if (order[i] == 'B') {
-            t += launches * (parents * 33.0 * unit / HBM + 3 * LAUNCH);
+            t += launches * (parents * 8.0 * step_elems(h, 11, 11, 11) / HBM + 3 * LAUNCH);
             parents *= 7.0;
             i += 1;
         } else {
             const bool keep = (rich >> i) & 1u;
-            t += launches * (parents * (keep ? 27.0 : 38.0) * unit / HBM + (keep ? 3 : 9) * LAUNCH);
+            t += launches * (parents * 8.0 * (keep ? step_elems(h, 8, 8, 11) : step_elems(h, 12, 12, 14)) / HBM + (keep ? 3 : 9) * LAUNCH);
             launches *= 7.0;
             i += 1;
         }
     }
-    // `parents` leaf products per launch, `launches` launches
-    t += launches * (parents * 2.0 * m * m * m / leaf_rate(m, parents) + LAUNCH);
-    if (np != n) t += 8.0 * (2.0 * (double)n * n + 4.0 * (double)np * np) / HBM;
+    // `parents` leaf products of shape h per launch, `launches` launches
+    t += launches * (parents * 2.0 * (double)h.m * (double)h.n * (double)h.k / leaf_rate((double)h.m, (double)h.n, (double)h.k, parents) + LAUNCH);
+    if (p.m != d.m || p.n != d.n || p.k != d.k)
+        t += 8.0 * ((double)d.m * d.k + (double)d.k * d.n + 2.0 * (double)d.m * d.n + (double)p.m * p.k + (double)p.k * p.n + 2.0 * (double)p.m * p.n) / HBM;
     return t;
 }
 
-double modelled_for_budget(int64_t n, int levels, int64_t budget, char* order)
+double modelled_for_budget(Dims d, int levels, int64_t budget, char* order)
 {
-    if (levels == 0) { order[0] = '\0'; return modelled_seconds(n, 0, order, 0); }
-    if (plan(n, levels, budget, order) != SW_OK) return -1.0;       // no step order of this depth fits
+    if (levels == 0) { order[0] = '\0'; return modelled_seconds(d, 0, order, 0); }
+    if (plan(d, levels, budget, order) != SW_OK) return -1.0;       // no step order of this depth fits
     uint32_t rich = 0;
     bool dbl = false;
-    const int64_t np = padded_n(n, levels);
-    const int64_t fixed = total_need(n, levels, order) - ws_need_bytes(np, order, 1);
-    choose_options(np, levels, order, budget - fixed, false, &rich, &dbl);
-    return modelled_seconds(n, levels, order, rich);
+    const Dims p{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)};
+    const int64_t fixed = total_need(d, levels, order) - ws_need_bytes(p, order, 1);
+    choose_options(p, levels, order, budget - fixed, false, &rich, &dbl);
+    return modelled_seconds(d, levels, order, rich);
 }
 
-int best_levels(int64_t n, int64_t budget)
+int best_levels(Dims d, int64_t budget)
 {
+    const int64_t lo = d.m < d.n ? (d.m < d.k ? d.m : d.k) : (d.n < d.k ? d.n : d.k);
     // below the measured crossover (classical wins at 2048, the recursion by a few percent at 4096) the
     // product is a handful of launch-bound kernels the model does not describe
-    if (n < 3072) return 0;
+    if (cbrt((double)d.m * (double)d.n * (double)d.k) < 3072.0) return 0;
     char order[SW_MAX_LEVELS + 1];
     int best = 0;
-    double best_t = modelled_for_budget(n, 0, budget, order);
-    for (int L = 1; L <= SW_MAX_LEVELS && ((int64_t)1 << L) <= n; ++L) {
-        if ((n >> L) < 64) break;                               // leaves below half a tile never pay
-        const double t = modelled_for_budget(n, L, budget, order);
+    double best_t = modelled_for_budget(d, 0, budget, order);
+    for (int L = 1; L <= SW_MAX_LEVELS && ((int64_t)1 << L) <= lo; ++L) {
+        if ((lo >> L) < 64) break;                              // leaves below half a tile never pay
+        const double t = modelled_for_budget(d, L, budget, order);
         if (t >= 0.0 && t < best_t) { best_t = t; best = L; }
     }
     return best;
 }
+int best_levels(int64_t n, int64_t budget) { return best_levels(Dims{n, n, n}, budget); }
 
 struct Dgemm {
     bool ta, tb;
@@ -173,7 +186,8 @@ struct Dgemm {
     const double* A; int64_t lda;
     const double* B; int64_t ldb;
     double* C; int64_t ldc;
-    int64_t s, ldp;
+    Dims s;                         // block shape: C blocks s.m x s.n, inner slices of s.k
+    int64_t ldp, lda_t, ldb_t;      // pitches of P (s.m x s.n), TA (s.m x s.k), TB (s.k x s.n)
     double *P, *TA, *TB;
     int levels;
     const char* schedule;
@@ -186,23 +200,23 @@ struct Dgemm {
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     bool ok() const { return err == hipSuccess && rc == SW_OK; }
 
-    // op(A)[i0 .. i0+rows, k0 .. k0+kc) as a row-major block
+    // op(A)[i0 .. i0+rows, k0 .. k0+kc) as a row-major block (rows <= s.m, kc <= s.k)
     Mat blockA(int64_t i0, int64_t rows, int64_t k0, int64_t kc)
     {
         if (!ta) return Mat{const_cast<double*>(A) + i0 * lda + k0, lda, 0, false};
         prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * rows * kc);
-        note(launch_transpose(A + k0 * lda + i0, lda, kc, rows, TA, ldp, st));
+        note(launch_transpose(A + k0 * lda + i0, lda, kc, rows, TA, lda_t, st));
         prof_end(prof, st);
-        return Mat{TA, ldp, 0, ldp > kc};
+        return Mat{TA, lda_t, 0, lda_t > kc};
     }
-    // op(B)[k0 .. k0+kc, j0 .. j0+cols)
+    // op(B)[k0 .. k0+kc, j0 .. j0+cols)  (kc <= s.k, cols <= s.n)
     Mat blockB(int64_t k0, int64_t kc, int64_t j0, int64_t cols)
     {
         if (!tb) return Mat{const_cast<double*>(B) + k0 * ldb + j0, ldb, 0, false};
         prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * kc * cols);
-        note(launch_transpose(B + j0 * ldb + k0, ldb, cols, kc, TB, ldp, st));
+        note(launch_transpose(B + j0 * ldb + k0, ldb, cols, kc, TB, ldb_t, st));
         prof_end(prof, st);
-        return Mat{TB, ldp, 0, ldp > cols};
+        return Mat{TB, ldb_t, 0, ldb_t > cols};
     }
     void fold(int64_t i0, int64_t rows, int64_t j0, int64_t cols, double b)
     {
@@ -210,106 +224,110 @@ struct Dgemm {
         note(launch_axpby(C + i0 * ldc + j0, ldc, P, ldp, rows, cols, alpha, b, st));
         prof_end(prof, st);
     }
-    void classical(int64_t rows, int64_t cols, int64_t kc, Mat a, Mat b, bool accumulate)
+    void classical(int64_t rows, int64_t cols, int64_t kc, Mat a, Mat b, Mat c, bool accumulate)
     {
         prof_begin(prof, st, SW_CLASS_PEEL, 2.0 * rows * cols * kc);
-        note(launch_gemm(rows, cols, kc, 1, a, b, Mat{P, ldp, 0, ldp > cols}, accumulate, st));
+        note(launch_gemm(rows, cols, kc, 1, a, b, c, accumulate, st));
         prof_end(prof, st);
     }
 
-    // an s x s block of C through the recursion, one k block after the other
+    // an s.m x s.n block of C through the recursion, one inner slice of s.k after the other
     void fast_block(int64_t i0, int64_t j0)
     {
-        const int64_t kb = K / s, rK = K - kb * s;
+        const int64_t kb = K / s.k, rK = K - kb * s.k;
         // a single product that needs no scaling and no old C goes straight into C
-        const bool direct = alpha == 1.0 && beta == 0.0 && kb == 1 && rK == 0;
+        const bool direct = alpha == 1.0 && beta == 0.0 && kb == 1;
+        const Mat out = direct ? Mat{C + i0 * ldc + j0, ldc, 0, false} : Mat{P, ldp, 0, ldp > s.n};
         for (int64_t k = 0; k < kb && ok(); ++k) {
-            const Mat a = blockA(i0, s, k * s, s), b = blockB(k * s, s, j0, s);
+            const Mat a = blockA(i0, s.m, k * s.k, s.k), b = blockB(k * s.k, s.k, j0, s.n);
             if (!ok()) return;
-            rc = gemm_impl(s, a.p, a.ld, b.p, b.ld, direct ? C + i0 * ldc + j0 : P, direct ? ldc : ldp, levels, schedule, rest,
-                           rest_bytes, st);
-            if (rc != SW_OK || direct) return;
+            rc = gemm_rect_impl(s, a.p, a.ld, b.p, b.ld, out.p, out.ld, levels, schedule, rest, rest_bytes, st);
+            if (rc != SW_OK) return;
             if (k == kb - 1 && rK > 0) {
-                const Mat ar = blockA(i0, s, kb * s, rK), br = blockB(kb * s, rK, j0, s);
-                classical(s, s, rK, ar, br, true);
+                const Mat ar = blockA(i0, s.m, kb * s.k, rK), br = blockB(kb * s.k, rK, j0, s.n);
+                classical(s.m, s.n, rK, ar, br, out, true);
             }
-            fold(i0, s, j0, s, k == 0 ? beta : 1.0);
+            if (!direct) fold(i0, s.m, j0, s.n, k == 0 ? beta : 1.0);
         }
     }
 
-    // a block of at most s x s of C through the classical product, K in slices of s
+    // a block of at most s.m x s.n of C through the classical product, K in slices of s.k
     void classical_block(int64_t i0, int64_t rows, int64_t j0, int64_t cols)
     {
-        for (int64_t k0 = 0; k0 < K && ok(); k0 += s) {
-            const int64_t kc = K - k0 < s ? K - k0 : s;
+        for (int64_t k0 = 0; k0 < K && ok(); k0 += s.k) {
+            const int64_t kc = K - k0 < s.k ? K - k0 : s.k;
             const Mat a = blockA(i0, rows, k0, kc), b = blockB(k0, kc, j0, cols);
-            classical(rows, cols, kc, a, b, k0 > 0);
+            classical(rows, cols, kc, a, b, Mat{P, ldp, 0, ldp > cols}, k0 > 0);
         }
         fold(i0, rows, j0, cols, beta);
     }
 
     void run()
     {
-        const int64_t mb = M / s, nb = N / s, rM = M - mb * s, rN = N - nb * s;
+        const int64_t mb = M / s.m, nb = N / s.n, rM = M - mb * s.m, rN = N - nb * s.n;
         for (int64_t i = 0; i < mb && ok(); ++i)
-            for (int64_t j = 0; j < nb && ok(); ++j) fast_block(i * s, j * s);
+            for (int64_t j = 0; j < nb && ok(); ++j) fast_block(i * s.m, j * s.n);
         if (rN > 0)                                                    // the right strip, all rows
-            for (int64_t i0 = 0; i0 < M && ok(); i0 += s) classical_block(i0, M - i0 < s ? M - i0 : s, nb * s, rN);
+            for (int64_t i0 = 0; i0 < M && ok(); i0 += s.m) classical_block(i0, M - i0 < s.m ? M - i0 : s.m, nb * s.n, rN);
         if (rM > 0)                                                    // the bottom strip left of it
-            for (int64_t j = 0; j < nb && ok(); ++j) classical_block(mb * s, rM, j * s, s);
+            for (int64_t j = 0; j < nb && ok(); ++j) classical_block(mb * s.m, rM, j * s.n, s.n);
     }
 };
 
-// largest multiple of 2^levels that fits the smallest dimension
-int64_t block_size(int64_t M, int64_t N, int64_t K, int levels)
+// extent / parts, rounded down to a multiple of 2^levels
+int64_t block_extent(int64_t extent, int parts, int levels)
 {
-    int64_t d = M < N ? M : N;
-    if (K < d) d = K;
-    return d - d % ((int64_t)1 << levels);
+    const int64_t raw = extent / parts;
+    return raw - raw % ((int64_t)1 << levels);
 }
 
-int64_t fixed_bytes(bool ta, bool tb, int64_t s) { return (1 + (ta ? 1 : 0) + (tb ? 1 : 0)) * ws_mat_elems(s) * (int64_t)sizeof(double); }
+// one temporary for a block of C, one more per transposed operand
+int64_t fixed_bytes(bool ta, bool tb, Dims s)
+{
+    return (ws_mat_elems(s.m, s.n) + (ta ? ws_mat_elems(s.m, s.k) : 0) + (tb ? ws_mat_elems(s.k, s.n) : 0)) * (int64_t)sizeof(double);
+}
 
-struct Choice { int64_t s; int levels; double seconds; };
+struct Choice { Dims s; int levels; double seconds; };
 
-// Among the block sizes floor(min(M, N, K) / j), j = 1 .. 8 (rounded down to a multiple of 2^levels), the one
-// with the least modelled time that fits the workspace: block products through the recursion at their
-// modelled time, everything else at the classical rate, one fold pass per block product.  levels < 0: the
-// depth is chosen per block size as well.  order_out: the step order to use when the caller gave none.
+// The block shape: M, N and K are each cut into 1 .. 4 equal parts (rounded down to a multiple of 2^levels;
+// what is left over, less than parts * 2^levels rows, columns or inner indices, goes through the classical
+// product).  Among the shapes whose workspace need fits, the one with the least modelled time: block products
+// through the recursion at their modelled time plus one fold pass, the rest at the classical rate.
+// levels < 0: the depth is chosen per shape as well.  order_out: the step order when the caller gave none.
 Choice choose_blocking(int64_t M, int64_t N, int64_t K, int levels, const char* schedule, bool ta, bool tb, int64_t ws_bytes,
                        char* order_out)
 {
-    int64_t d = M < N ? M : N;
-    if (K < d) d = K;
-    Choice best{0, 0, 0.0};
+    Choice best{Dims{0, 0, 0}, 0, 0.0};
     char order[SW_MAX_LEVELS + 1];
-    for (int j = 1; j <= 8; ++j) {
-        const int64_t raw = d / j;
-        if (raw == 0) break;
-        int L = levels;
-        if (L < 0) {
-            const int64_t room0 = ws_bytes - fixed_bytes(ta, tb, raw);
-            L = room0 > 0 ? best_levels(raw, room0) : 0;
-        }
-        const int64_t s = raw - raw % ((int64_t)1 << L);
-        if (s == 0) continue;
-        const int64_t room = ws_bytes - fixed_bytes(ta, tb, s);
-        if (room < 0) continue;
-        double tb_ = -1.0;
-        if (schedule && *schedule) {
-            if (total_need(s, L, schedule) <= room) { tb_ = modelled_seconds(s, L, schedule, 0); strcpy(order, schedule); }
-        } else {
-            tb_ = modelled_for_budget(s, L, room, order);
-        }
-        if (tb_ < 0.0) continue;
-        const double blocks = (double)(M / s) * (double)(N / s) * (double)(K / s);
-        const double rest = 2.0 * (double)M * N * K - blocks * 2.0 * (double)s * s * s;
-        const double t = blocks * (tb_ + 3.0 * 8.0 * (double)s * s / 5.0e12) + rest / 75e12;
-        if (best.s == 0 || t < best.seconds) {
-            best = Choice{s, L, t};
-            strcpy(order_out, order);
-        }
-    }
+    for (int pm = 1; pm <= 4; ++pm)
+        for (int pn = 1; pn <= 4; ++pn)
+            for (int pk = 1; pk <= 4; ++pk) {
+                int L = levels;
+                if (L < 0) {
+                    const Dims raw{M / pm, N / pn, K / pk};
+                    if (raw.m == 0 || raw.n == 0 || raw.k == 0) continue;
+                    const int64_t room0 = ws_bytes - fixed_bytes(ta, tb, raw);
+                    L = room0 > 0 ? best_levels(raw, room0) : 0;
+                }
+                const Dims s{block_extent(M, pm, L), block_extent(N, pn, L), block_extent(K, pk, L)};
+                if (s.m == 0 || s.n == 0 || s.k == 0) continue;
+                const int64_t room = ws_bytes - fixed_bytes(ta, tb, s);
+                if (room < 0) continue;
+                double tblock = -1.0;
+                if (schedule && *schedule) {
+                    if (total_need(s, L, schedule) <= room) { tblock = modelled_seconds(s, L, schedule, 0); strcpy(order, schedule); }
+                } else {
+                    tblock = modelled_for_budget(s, L, room, order);
+                }
+                if (tblock < 0.0) continue;
+                const double blocks = (double)(M / s.m) * (double)(N / s.n) * (double)(K / s.k);
+                const double rest = 2.0 * (double)M * N * K - blocks * 2.0 * (double)s.m * s.n * s.k;
+                const double t = blocks * (tblock + 3.0 * 8.0 * (double)s.m * s.n / 5.0e12) + rest / 75e12;
+                if (best.s.m == 0 || t < best.seconds) {
+                    best = Choice{s, L, t};
+                    strcpy(order_out, order);
+                }
+            }
     return best;
 }
 
@@ -345,7 +363,7 @@ double sw_model_seconds(int64_t n, int levels, int64_t budget_bytes)
         return -1.0;
     }
     char order[SW_MAX_LEVELS + 1];
-    const double t = modelled_for_budget(n, levels, budget_bytes, order);
+    const double t = modelled_for_budget(Dims{n, n, n}, levels, budget_bytes, order);
     if (t < 0.0) set_error("no step order of depth %d fits %lld bytes", levels, (long long)budget_bytes);
     return t;
 }
@@ -356,9 +374,9 @@ int64_t sw_plan_memory_dgemm(int transa, int transb, int64_t M, int64_t N, int64
     if (rc != SW_OK) return rc;
     if (levels < 0) { set_error("sw_plan_memory_dgemm needs an explicit depth (sw_plan_levels gives one)"); return SW_EINVAL; }
     if (M == 0 || N == 0 || K == 0) return 0;
-    const int64_t s = block_size(M, N, K, levels);
-    if (s == 0) { set_error("2^levels = %lld exceeds the smallest dimension", (long long)((int64_t)1 << levels)); return SW_EINVAL; }
-    const int64_t inner = sw_plan_memory(s, levels, schedule);
+    const Dims s{block_extent(M, 1, levels), block_extent(N, 1, levels), block_extent(K, 1, levels)};
+    if (s.m == 0 || s.n == 0 || s.k == 0) { set_error("2^levels = %lld exceeds the smallest dimension", (long long)((int64_t)1 << levels)); return SW_EINVAL; }
+    const int64_t inner = sw_plan_memory_rect(s.m, s.n, s.k, levels, schedule);
     if (inner < 0) return inner;
     return fixed_bytes(transa != 0, transb != 0, s) + inner;
 }
@@ -395,22 +413,19 @@ int sw_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, double alp
         return SW_EINVAL;
     }
     if (levels < 0) schedule = nullptr;
-    if (levels >= 0 && block_size(M, N, K, levels) == 0) {
+    if (levels >= 0 && (block_extent(M, 1, levels) == 0 || block_extent(N, 1, levels) == 0 || block_extent(K, 1, levels) == 0)) {
         set_error("2^levels = %lld exceeds the smallest dimension", (long long)((int64_t)1 << levels));
         return SW_EINVAL;
     }
-    // Block size (and depth, if left open) by the cost model: the smallest dimension cut into 1 .. 8 blocks;
-    // fewer, larger blocks recurse deeper, more blocks leave less to the classical remainder products.
+    // Block shape (and depth, if left open) by the cost model
     char chosen[SW_MAX_LEVELS + 1] = "";
     const Choice ch = choose_blocking(M, N, K, levels, schedule, ta, tb, ws ? ws_bytes : 0, chosen);
-    if (ch.s == 0) {
-        const int64_t s1 = block_size(M, N, K, levels < 0 ? 0 : levels);
-        set_error("workspace of %lld bytes is too small: a block size of %lld needs %lld", (long long)(ws ? ws_bytes : 0), (long long)s1,
-                  (long long)(fixed_bytes(ta, tb, s1) + total_need(s1, levels < 0 ? 0 : levels,
-                                                                   schedule && *schedule ? schedule : std::string((size_t)(levels < 0 ? 0 : levels), 'D').c_str())));
+    if (ch.s.m == 0) {
+        set_error("workspace of %lld bytes is too small for any block shape of %lld x %lld x %lld", (long long)(ws ? ws_bytes : 0),
+                  (long long)M, (long long)N, (long long)K);
         return SW_ENOMEM;
     }
-    const int64_t s = ch.s;
+    const Dims s = ch.s;
     levels = ch.levels;
     if (!schedule || !*schedule) schedule = chosen;
     const int64_t fixed = fixed_bytes(ta, tb, s);
@@ -425,12 +440,12 @@ int sw_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, double alp
     g.M = M; g.N = N; g.K = K;
     g.alpha = alpha; g.beta = beta;
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
-    g.s = s; g.ldp = ws_ld(s);
+    g.s = s;
+    g.ldp = ws_ld(s.n); g.lda_t = ws_ld(s.k); g.ldb_t = ws_ld(s.n);
     double* w = (double*)ws;
-    const int64_t e = ws_mat_elems(s);
-    g.P = w; w += e;
-    g.TA = ta ? w : nullptr; if (ta) w += e;
-    g.TB = tb ? w : nullptr; if (tb) w += e;
+    g.P = w; w += ws_mat_elems(s.m, s.n);
+    g.TA = ta ? w : nullptr; if (ta) w += ws_mat_elems(s.m, s.k);
+    g.TB = tb ? w : nullptr; if (tb) w += ws_mat_elems(s.k, s.n);
     g.levels = levels;
     g.schedule = schedule;
     g.rest = w;

@@ -94,9 +94,8 @@ def main():
                                         args.beta, C, N, args.levels, None), args.iters, args.warmup)
         sw.sw_set_workspace(None)
         eff = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-        d = min(M, N, K)
         out = {"kernel": "sw_dgemm", "M": M, "N": N, "K": K, "transa": args.transa, "transb": args.transb,
-               "levels": args.levels if args.levels >= 0 else f"auto ({sw.sw_plan_levels(d, ws.numel())} for a {d} block)",
+               "levels": args.levels if args.levels >= 0 else "auto (block shape and depth by the library's cost model)",
                "avg_ms": round(ms, 3), "achieved": round(eff, 2), "unit": "effective TFLOP/s (2MNK/t)",
                "peak": FP64_MFMA_PEAK_TFLOPS, "frac": round(eff / FP64_MFMA_PEAK_TFLOPS, 4), "bound": "mfma"}
     elif args.kernel in ("pre_add", "post_add"):

@@ -214,14 +214,18 @@ def test_plan_levels_and_dgemm_memory():
         assert L >= prev
         prev = L
         assert sw.sw_plan_memory(n, L, None) <= big
-    # dgemm workspace: the recursion's own on the s x s block plus one temporary, one more per transposed operand
-    M, N, K, L = 5000, 3000, 4000, 3
-    s = 3000
-    inner = sw.sw_plan_memory(s, L, "DBB")
-    one = sw.sw_plan_memory_dgemm(0, 0, M, N, K, L, "DBB") - inner
-    assert one >= 8 * s * s
-    assert sw.sw_plan_memory_dgemm(1, 0, M, N, K, L, "DBB") - inner == 2 * one
-    assert sw.sw_plan_memory_dgemm(1, 1, M, N, K, L, "DBB") - inner == 3 * one
+    # dgemm workspace (the largest block shape it considers: the whole product, rounded down to multiples of
+    # 2^levels): the recursion's own plus a temporary for C's block and one more per transposed operand
+    def elems(rows, cols):
+        ld = (cols + 15) // 16 * 16
+        ld += 16 if ld >= 256 and ld % 256 == 0 else 0
+        return (ld * rows + 31) // 32 * 32
+    M, N, K, L = 5003, 3001, 4005, 3
+    sm, sn, sk = 5000, 3000, 4000
+    inner = sw.sw_plan_memory_rect(sm, sn, sk, L, "DBB")
+    assert sw.sw_plan_memory_dgemm(0, 0, M, N, K, L, "DBB") == inner + 8 * elems(sm, sn)
+    assert sw.sw_plan_memory_dgemm(1, 0, M, N, K, L, "DBB") == inner + 8 * (elems(sm, sn) + elems(sm, sk))
+    assert sw.sw_plan_memory_dgemm(1, 1, M, N, K, L, "DBB") == inner + 8 * (elems(sm, sn) + elems(sm, sk) + elems(sk, sn))
     with pytest.raises(sw.SwError):
         sw.sw_plan_memory_dgemm(0, 0, 64, 64, 3, 2, "BB")
 
