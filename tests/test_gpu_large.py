@@ -138,3 +138,25 @@ def test_peeled_size_near_configuration_5(oracle):
 def test_configuration_5_integer(oracle):
     cfg = inputs.CONFIGS[4]
     _check_product(oracle, cfg, "integer", None)
+
+
+def test_large_rectangular_product_freivalds():
+    """30000 x 20000 x 25000 through four rectangular steps in the planner's order, integer-valued operands:
+    C x must equal A (B x) exactly for 8 random +-1 vectors (every value involved is an exact integer)."""
+    M, N, K, levels = 30000, 20000, 25000, 4
+    A = torch.empty((M, K), dtype=torch.float64, device=DEV)
+    B = torch.empty((K, N), dtype=torch.float64, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    A.copy_(torch.randint(-8, 9, (M, K), generator=g, device=DEV, dtype=torch.int32))
+    B.copy_(torch.randint(-8, 9, (K, N), generator=g, device=DEV, dtype=torch.int32))
+    C = torch.full((M, N), float("nan"), dtype=torch.float64, device=DEV)
+    free, _ = torch.cuda.mem_get_info()
+    ws = torch.empty(int(min(free - (2 << 30), 40 << 30)), dtype=torch.uint8, device=DEV)
+    sw.sw_gemm_rect(M, N, K, A, K, B, N, C, N, levels, None, ws)
+    torch.cuda.synchronize()
+    gc_ = torch.Generator(device="cpu").manual_seed(9)
+    for _ in range(8):
+        x = (torch.randint(0, 2, (N,), generator=gc_, dtype=torch.int64) * 2 - 1).to(torch.float64).to(DEV)
+        assert torch.equal(torch.mv(C, x), torch.mv(A, torch.mv(B, x)))
+    del ws, A, B, C
+    _free()
