@@ -1,13 +1,14 @@
 // The product as a drop-in general matrix multiply: C <- alpha * op(A) * op(B) + beta * C on rectangular
 // row-major operands, op(X) = X or its transpose, and the choice of the recursion depth by a cost model.
 //
-// The fast recursion works on square blocks.  With s the largest multiple of 2^levels that fits min(M, N, K),
-// op(A), op(B), C are cut into s x s blocks; every block product goes through the Strassen-Winograd
-// recursion into a temporary P and is folded into C by one pass (C_ij <- alpha * P + beta' * C_ij, beta' =
-// beta for the first k block and 1 afterwards).  What is left over in each dimension (less than s rows,
-// columns or inner indices) goes through the classical MFMA product, the K remainder being accumulated into P
-// before the fold.  Transposed operands are transposed block by block into a workspace buffer, so the
-// recursion and the leaf kernel always see row-major blocks.
+// M, N and K are each cut into 1 .. 4 equal parts (multiples of 2^levels), which gives blocks of
+// s.m x s.n x s.k; every block product goes through the Strassen-Winograd recursion on rectangular operands
+// into a temporary P and is folded into C by one pass (C_ij <- alpha * P + beta' * C_ij, beta' = beta for the
+// first inner slice and 1 afterwards; straight into C when alpha = 1, beta = 0 and K is one slice).  What is
+// left over in each dimension (fewer than 4 * 2^levels rows, columns or inner indices) goes through the
+// classical MFMA product, the K remainder being accumulated before the fold.  Transposed operands are
+// transposed block by block into a workspace buffer, so the recursion and the leaf kernel always see
+// row-major blocks.  Block shape and depth are chosen by the cost model below.
 #include <math.h>
 #include <string.h>
 
