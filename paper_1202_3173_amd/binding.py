@@ -30,12 +30,18 @@ _lib = None
 
 
 def lib():
-    """Load libsw_gemm.so (built by __graft_entry__.build()); raise if it is not there."""
+    """Load libsw_gemm.so.  If nothing is built yet (a fresh checkout) it is compiled once with hipcc; if that
+    fails, or a library named by SW_GEMM_LIB is missing, this raises: there is no other implementation."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        if os.environ.get("SW_GEMM_LIB"):
+            raise RuntimeError(f"{LIB_PATH} (SW_GEMM_LIB) does not exist")
+        from . import build as _build
+        _build.build()
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing and could not be built: run `python -c 'import __graft_entry__ as g; g.build()'`")
     L = ctypes.CDLL(LIB_PATH)
     i64, vp, cp, ci, dbl = ctypes.c_int64, ctypes.c_void_p, ctypes.c_char_p, ctypes.c_int, ctypes.c_double
     sig = {

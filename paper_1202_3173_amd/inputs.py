@@ -132,6 +132,9 @@ def _fill():
     global _fill_lib
     if _fill_lib is None:
         if not os.path.exists(FILL_LIB_PATH):
+            from . import build as _build          # a fresh checkout: compile once
+            _build.build()
+        if not os.path.exists(FILL_LIB_PATH):
             raise RuntimeError(f"{FILL_LIB_PATH} is not built; run __graft_entry__.build()")
         L = ctypes.CDLL(FILL_LIB_PATH)
         L.sw_inputs_fill.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
