@@ -56,8 +56,9 @@ int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t
 /* The same recursion on a rectangular product: C (M x N) = A (M x K) * B (K x N), row-major with leading
  * dimensions lda >= K, ldb >= N, ldc >= N.  Every step halves all three extents: the operands T are
  * M/2 x K/2, S are K/2 x N/2, the products Q are M/2 x N/2 (Appendix A holds for any conformal 2 x 2
- * blocking).  Extents that 2^levels does not divide are zero-padded into workspace copies (peeling is for
- * square products only).  Otherwise as sw_gemm_ex; workspace_bytes >= sw_plan_memory_rect.
+ * blocking).  Extents that 2^levels does not divide are zero-padded into workspace copies or, with
+ * sw_set_odd_mode(SW_ODD_PEEL), peeled (recursion on the previous multiples, up to three thin classical
+ * products for the rest).  Otherwise as sw_gemm_ex; workspace_bytes >= sw_plan_memory_rect.
  * Errors as sw_gemm_ex; SW_EINVAL also when 2^levels exceeds the smallest extent or K == 0 with M, N > 0. */
 int sw_gemm_rect(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, const double* B, int64_t ldb, double* C,
                  int64_t ldc, int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);

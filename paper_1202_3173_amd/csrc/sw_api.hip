@@ -111,12 +111,17 @@ int check_shape(int64_t n, int levels)
 // Total workspace bytes for (n, schedule): with padding the recursion runs on the next multiple of 2^levels
 // and needs padded copies of A, B, C; with peeling it runs in place on the previous multiple.
 static Dims padded_dims(Dims d, int levels) { return Dims{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)}; }
+static Dims floor_dims(Dims d, int levels)
+{
+    const int64_t q = (int64_t)1 << levels;
+    return Dims{d.m - d.m % q, d.n - d.n % q, d.k - d.k % q};
+}
 
 int64_t total_need(Dims d, int levels, const char* sched)
 {
     if (d.m == 0 || d.n == 0 || d.k == 0) return 0;
-    // peeling is defined for square products only (one peel at the top, three thin classical products)
-    if (g_odd_mode == SW_ODD_PEEL && d.cube()) return ws_need_bytes(d.m - d.m % ((int64_t)1 << levels), sched, 1);
+    // peeling: the recursion runs in place on the previous multiples of 2^levels, no copies
+    if (g_odd_mode == SW_ODD_PEEL) return ws_need_bytes(floor_dims(d, levels), sched, 1);
     const Dims p = padded_dims(d, levels);
     int64_t bytes = ws_need_bytes(p, sched, 1);
     if (p.m != d.m || p.n != d.n || p.k != d.k)
@@ -538,9 +543,9 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
     ex.ws_bytes = ws_bytes;
     ex.sched = schedule;
     ex.levels = levels;
-    const int64_t q = (int64_t)1 << levels;
-    const bool peel = g_odd_mode == SW_ODD_PEEL && d.cube() && d.m % q != 0;
-    const Dims rec = peel ? Dims{d.m - d.m % q, d.m - d.m % q, d.m - d.m % q} : padded_dims(d, levels);
+    const Dims lead = floor_dims(d, levels);
+    const bool peel = g_odd_mode == SW_ODD_PEEL && (lead.m != d.m || lead.n != d.n || lead.k != d.k);
+    const Dims rec = peel ? lead : padded_dims(d, levels);
     {
         // spend what the workspace has beyond the minimum: first on a second set of the buffers next to the
         // leaves (so that additions and leaf products of consecutive launches overlap), then on the rich form
@@ -556,19 +561,20 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
     if (peel) {
-        // Peeling (Section 3.1 names it beside padding), square products only: the leading n0 x n0 blocks, n0
-        // the previous multiple of 2^levels, go through the recursion in place; the r < 2^levels peeled rows
-        // and columns are finished by three thin classical products on the same MFMA kernel.
-        const int64_t n = d.m, r = n % q, n0 = n - r;
+        // Peeling (Section 3.1 names it beside padding): the leading blocks, whose extents are the previous
+        // multiples of 2^levels, go through the recursion in place; the fewer than 2^levels peeled rows, columns
+        // and inner indices are finished by up to three thin classical products on the same MFMA kernel.
+        const int64_t rm = d.m - rec.m, rn = d.n - rec.n, rk = d.k - rec.k;
         ex.mul(a, b, c, rec, 0, 1);                                  // C11  = A11 * B11
-        const Mat a12{a.p + n0, lda, 0}, b21{b.p + n0 * ldb, ldb, 0};
-        const Mat bright{b.p + n0, ldb, 0}, c12{c.p + n0, ldc, 0};
-        const Mat abot{a.p + n0 * lda, lda, 0}, cbot{c.p + n0 * ldc, ldc, 0};
-        ex.op(S_POST, SW_CLASS_PEEL, 2.0 * r * ((double)n0 * n0 + 2.0 * (double)n * n0 + (double)n * r),
-              {rng(a, n, n), rng(b, n, n)}, {rng(c, n, n)}, [&](hipStream_t st) {
-                  hipError_t e1 = launch_gemm(n0, n0, r, 1, a12, b21, c, true, st);          // C11 += A12 * B21
-                  hipError_t e2 = launch_gemm(n0, r, n, 1, a, bright, c12, false, st);       // C12  = [A11 A12] * [B12; B22]
-                  hipError_t e3 = launch_gemm(r, n, n, 1, abot, b, cbot, false, st);         // [C21 C22] = [A21 A22] * B
+        const Mat a12{a.p + rec.k, lda, 0}, b21{b.p + rec.k * ldb, ldb, 0};
+        const Mat bright{b.p + rec.n, ldb, 0}, c12{c.p + rec.n, ldc, 0};
+        const Mat abot{a.p + rec.m * lda, lda, 0}, cbot{c.p + rec.m * ldc, ldc, 0};
+        ex.op(S_POST, SW_CLASS_PEEL,
+              2.0 * ((double)rec.m * rec.n * rk + (double)rec.m * rn * d.k + (double)rm * d.n * d.k),
+              {rng(a, d.m, d.k), rng(b, d.k, d.n)}, {rng(c, d.m, d.n)}, [&](hipStream_t st) {
+                  hipError_t e1 = rk ? launch_gemm(rec.m, rec.n, rk, 1, a12, b21, c, true, st) : hipSuccess;      // C11 += A12 * B21
+                  hipError_t e2 = rn ? launch_gemm(rec.m, rn, d.k, 1, a, bright, c12, false, st) : hipSuccess;    // C12  = [A11 A12] * [B12; B22]
+                  hipError_t e3 = rm ? launch_gemm(rm, d.n, d.k, 1, abot, b, cbot, false, st) : hipSuccess;       // [C21 C22] = [A21 A22] * B
                   return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
               });
     } else {

@@ -96,6 +96,7 @@ def test_seeded_sweep_is_exact():
             M, N, K = (int(rng.integers(lo, 450)) for _ in range(3))
             schedule = "".join(rng.choice(["B", "D"]) for _ in range(levels))
             sw.sw_set_overlap(bool(rng.integers(0, 2)))
+            sw.sw_set_odd_mode(sw.SW_ODD_PEEL if rng.integers(0, 2) else sw.SW_ODD_PAD)
             A = rect(M, K, 7000 + case, 0, "integer")
             B = rect(K, N, 7000 + case, 1, "integer")
             pads = tuple(int(x) for x in rng.integers(0, 3, size=3))
@@ -103,6 +104,26 @@ def test_seeded_sweep_is_exact():
             assert np.array_equal(got, A @ B), (case, M, N, K, levels, schedule, pads)
     finally:
         sw.sw_set_overlap(True)
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
+@pytest.mark.parametrize("M,N,K,levels,schedule", [(333, 203, 111, 2, "BD"), (130, 517, 259, 3, "DBB"), (1001, 64, 70, 1, "B"),
+                                                   (64, 64, 67, 2, "DD"), (67, 64, 64, 2, "BB"), (64, 67, 64, 2, "DB")])
+def test_peeling_needs_no_copies_and_is_exact(M, N, K, levels, schedule):
+    A = rect(M, K, 11, 0, "integer")
+    B = rect(K, N, 11, 1, "integer")
+    q = 1 << levels
+    try:
+        sw.sw_set_odd_mode(sw.SW_ODD_PEEL)
+        # the workspace is that of the leading multiples of 2^levels: no padded copies
+        assert sw.sw_plan_memory_rect(M, N, K, levels, schedule) == sw.sw_plan_memory_rect(M - M % q, N - N % q, K - K % q, levels, schedule)
+        assert np.array_equal(run(A, B, levels, schedule, pads=(1, 2, 0)), A @ B)
+        Ar = rect(M, K, 12, 0, "uniform")
+        Br = rect(K, N, 12, 1, "uniform")
+        ref = oracle_dgemm.dgemm(False, False, 1.0, Ar, Br, 0.0, np.zeros((M, N)))
+        assert np.max(np.abs(run(Ar, Br, levels, schedule) - ref)) <= 1e-10 * K * np.max(np.abs(Ar)) * np.max(np.abs(Br))
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
 
 
 def test_errors():
