@@ -96,6 +96,45 @@ double sw_oracle_entry(int64_t n, const double *A_row_i, const double *B_col_j, 
     return (double)s;
 }
 
+/* Strips of the product by its definition (Algorithm 1, Ensure), for checking
+ * a large result where the whole product is out of reach: every entry gets its
+ * n terms in ascending k, each a rounded product followed by a rounded sum,
+ * exactly as in `classical` above, so a strip equals the same rows (columns)
+ * of sw_oracle_naive bit for bit.
+ *
+ * Row strip:    C_rows (r x n) = A_rows (r x n) * B (n x n), where A_rows holds
+ *               r chosen rows of A one after the other (leading dimension n).
+ * Column strip: C_cols (n x c) = A (n x n) * B_cols (n x c), where B_cols holds
+ *               c chosen columns of B side by side (leading dimension c).
+ * All matrices dense, row-major, host memory, caller-owned. */
+__attribute__((target_clones("avx2", "default")))
+static void strip(const double *A, int64_t lda, const double *B, int64_t ldb,
+                  double *C, int64_t ldc, int64_t rows, int64_t cols, int64_t n)
+{
+    for (int64_t i = 0; i < rows; ++i) {
+        double *c = C + i * ldc;
+        const double a0 = A[i * lda];
+        for (int64_t j = 0; j < cols; ++j) c[j] = a0 * B[j];
+        for (int64_t k = 1; k < n; ++k) {
+            const double a = A[i * lda + k];
+            const double *b = B + k * ldb;
+            for (int64_t j = 0; j < cols; ++j) c[j] = c[j] + a * b[j];
+        }
+    }
+}
+
+void sw_oracle_row_strip(int64_t n, int64_t r, const double *A_rows, const double *B, double *C_rows)
+{
+    if (n <= 0 || r <= 0) return;
+    strip(A_rows, n, B, n, C_rows, n, r, n, n);
+}
+
+void sw_oracle_col_strip(int64_t n, int64_t c, const double *A, const double *B_cols, double *C_cols)
+{
+    if (n <= 0 || c <= 0) return;
+    strip(A, n, B_cols, c, C_cols, c, n, c, n);
+}
+
 /* ---- matrix add / subtract on row-major views ---------------------------- */
 
 __attribute__((target_clones("avx2", "default")))

@@ -40,6 +40,10 @@ def lib():
         L.sw_oracle_naive.restype = None
         L.sw_oracle_entry.argtypes = [ctypes.c_int64, dp, dp, ctypes.c_int64]
         L.sw_oracle_entry.restype = ctypes.c_double
+        L.sw_oracle_row_strip.argtypes = [ctypes.c_int64, ctypes.c_int64, dp, dp, dp]
+        L.sw_oracle_row_strip.restype = None
+        L.sw_oracle_col_strip.argtypes = [ctypes.c_int64, ctypes.c_int64, dp, dp, dp]
+        L.sw_oracle_col_strip.restype = None
         L.sw_oracle_reset_counters.argtypes = []
         L.sw_oracle_reset_counters.restype = None
         L.sw_oracle_get_counters.argtypes = [ctypes.POINTER(Counters)]
@@ -93,6 +97,30 @@ def entry(a_row, b_col):
     if a_row.shape != b_col.shape or a_row.ndim != 1:
         raise ValueError("row and column must be 1-D and of equal length")
     return float(lib().sw_oracle_entry(a_row.shape[0], _ptr(a_row), _ptr(b_col), 1))
+
+
+def row_strip(A_rows, B):
+    """Rows of A @ B by the definition (k ascending): A_rows is r x n (chosen rows of A), B is n x n."""
+    A_rows = np.ascontiguousarray(A_rows, dtype=np.float64)
+    B = _square(B, "B")
+    n = B.shape[0]
+    if A_rows.ndim != 2 or A_rows.shape[1] != n:
+        raise ValueError("A_rows must be r x n")
+    C = np.empty_like(A_rows)
+    lib().sw_oracle_row_strip(n, A_rows.shape[0], _ptr(A_rows), _ptr(B), _ptr(C))
+    return C
+
+
+def col_strip(A, B_cols):
+    """Columns of A @ B by the definition (k ascending): A is n x n, B_cols is n x c (chosen columns of B)."""
+    A = _square(A, "A")
+    B_cols = np.ascontiguousarray(B_cols, dtype=np.float64)
+    n = A.shape[0]
+    if B_cols.ndim != 2 or B_cols.shape[0] != n:
+        raise ValueError("B_cols must be n x c")
+    C = np.empty_like(B_cols)
+    lib().sw_oracle_col_strip(n, B_cols.shape[1], _ptr(A), _ptr(B_cols), _ptr(C))
+    return C
 
 
 def reset_counters():

@@ -11,7 +11,11 @@ wrong sign or quadrant, a transposed operand, a wrong count) fails it:
   * traversal memory against Mem_UM (Section 3.3.1) and Mem_LM (Section 3.4.1);
   * the tables exactly as printed are shown NOT to give a product (reading R1);
   * floating-point results against an extended-precision product, inside the
-    norm-wise bound form of Section 6.1.
+    norm-wise bound form of Section 6.1;
+  * row and column strips of the definition (used to referee large results):
+    exact integers against a pure-Python brute force and int64 matmul, bit
+    equality with the same rows / columns of the whole naive product, and
+    asymmetric operands (a strip of A*B is not a strip of B*A or of a transpose).
 """
 import math
 import os
@@ -250,3 +254,46 @@ def test_float_result_close_to_extended_precision_product(oracle, dist):
     # levels = 0 obeys the tighter component-wise bound n*eps*|A||B| of the classical algorithm
     comp = n * np.finfo(float).eps * (np.abs(A) @ np.abs(B))
     assert np.all(np.abs(oracle.gemm(A, B, 0) - ref) <= comp)
+
+
+# ---- strips of the definition ----------------------------------------------------
+
+def test_strips_are_exact_on_integers_vs_pure_python(oracle):
+    n = 9
+    A, B = int_pair(n, 77)
+    ref = brute(A.tolist(), B.tolist())
+    rows, cols = [0, 4, 8, 3], [8, 0, 5]
+    R = oracle.row_strip(A[rows], B)
+    assert R.tolist() == [[float(v) for v in ref[i]] for i in rows]
+    K = oracle.col_strip(A, np.ascontiguousarray(B[:, cols]))
+    assert K.tolist() == [[float(ref[i][j]) for j in cols] for i in range(n)]
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 130, 257])
+def test_strips_equal_the_whole_naive_product_bit_for_bit(oracle, n):
+    """Same terms, same order, same rounding as sw_oracle_naive: equality, not closeness, on non-integer data;
+    and exact against int64 matmul on integers."""
+    A = inputs.matrix(n, 5, 0, "uniform") * (1.0 + np.arange(n)[:, None])        # rows of different size
+    B = inputs.matrix(n, 5, 1, "uniform")
+    whole = oracle.naive(A, B)
+    rng = np.random.default_rng(n)
+    rows = rng.permutation(n)[: max(1, n // 3)]
+    cols = rng.permutation(n)[: max(1, n // 4)]
+    assert np.array_equal(oracle.row_strip(A[rows], B), whole[rows])
+    assert np.array_equal(oracle.col_strip(A, np.ascontiguousarray(B[:, cols])), whole[:, cols])
+    Ai, Bi = int_pair(n, 9 + n)
+    exact = (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64)
+    assert np.array_equal(oracle.row_strip(Ai[rows], Bi), exact[rows])
+    assert np.array_equal(oracle.col_strip(Ai, np.ascontiguousarray(Bi[:, cols])), exact[:, cols])
+
+
+def test_strips_do_not_swap_or_transpose_operands(oracle):
+    n = 6
+    A = np.arange(1.0, n * n + 1).reshape(n, n)
+    B = np.triu(np.ones((n, n))) * np.arange(1.0, n + 1)[None, :]
+    ref = A.astype(np.int64) @ B.astype(np.int64)
+    assert not np.array_equal(ref, (B @ A)) and not np.array_equal(ref, A.T @ B) and not np.array_equal(ref, A @ B.T)
+    assert np.array_equal(oracle.row_strip(A[[1, 4]], B), ref[[1, 4]].astype(np.float64))
+    assert np.array_equal(oracle.col_strip(A, np.ascontiguousarray(B[:, [0, 5, 2]])), ref[:, [0, 5, 2]].astype(np.float64))
+    # a strip of one row and one column meet in the single entry the long-double routine gives on integers
+    assert oracle.row_strip(A[[3]], B)[0, 2] == oracle.entry(A[3], np.ascontiguousarray(B[:, 2])) == float(ref[3, 2])
