@@ -261,6 +261,33 @@ int sw_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols,
 int sw_profile_enable(int on);
 int sw_profile_read(double* ms, int64_t* launches, double* work);
 
+/* ---- verification of the executor's ordering, on the host (no GPU needed) ---------------------------------- */
+
+/* A record-only run of sw_gemm_rect: the executor walks the same recursion (Algorithm 2, procedures BFS and DFS)
+ * for this shape, step order, workspace size and settings, but launches nothing and makes no HIP call.  It
+ * writes down, in submission order, every kernel it would launch with the memory that kernel touches -- taken
+ * from the launch arguments, not from what the executor declared to its dependency tracker --, every event it
+ * would record, every stream wait it would issue and every buffer it takes from the workspace.  A checker can
+ * rebuild happens-before from the record and look for conflicting accesses that no chain of waits orders.
+ * Operands have synthetic addresses: A at 2^40, B at 2 * 2^40, C at 3 * 2^40, the workspace at 4 * 2^40.
+ * overlap, odd_mode: as sw_set_overlap / sw_set_odd_mode would set them (the process-wide settings are not read).
+ * withhold: -1, or the number (counted over the call, reads before writes) of ONE range that is kept from the
+ * dependency tracker although its kernel still touches it: a planted mistake for testing the checker.
+ * log: HOST buffer of log_words 64-bit words, may be NULL.  Returns the number of words of the whole record
+ * (only the first log_words are written) or a negative error code.  Records:
+ *   1, stream, kernel kind, nr, nw, then nr read and nw written footprints of 6 words each:
+ *      address, rows, cols, leading dimension, count, stride (count matrices of rows x cols doubles, in elements)
+ *   2, stream, slot                 an event is recorded on `stream` (slot -1: the entry event)
+ *   3, stream, event stream, slot   `stream` waits for the event (event stream, slot) as last recorded
+ *   4, offset, bytes                a buffer is taken from the workspace stack
+ *   5, offset                       the stack is cut back to `offset`
+ *   6, tracked                      the tracker held `tracked` unsettled accesses and fell back to ordering every
+ *                                   stream after every other (the waits follow as records of kind 3)
+ * Streams: 0 the caller's, 1 and 2 the library's.  Kernel kinds: 0 pre-addition, 1 post-addition, 2 and 3 the
+ * fused two-step forms, 4 element-wise, 5 DFS post block, 6 pad copy, 7 product. */
+int64_t sw_trace_gemm(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int levels, const char* schedule,
+                      int64_t workspace_bytes, int overlap, int odd_mode, int64_t withhold, int64_t* log, int64_t log_words);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
            "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
-           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect")
+           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm")
 
 
 class SwError(RuntimeError):
@@ -52,6 +52,7 @@ def lib():
         "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
         "sw_gemm_rect": (ci, [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
         "sw_plan_memory_rect": (i64, [i64, i64, i64, ci, cp]),
+        "sw_trace_gemm": (i64, [i64, i64, i64, i64, i64, i64, ci, cp, i64, ci, ci, i64, ctypes.POINTER(i64), i64]),
         "sw_dgemm": (ci, [ci, ci, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, cp]),
         "sw_plan_memory_dgemm": (i64, [ci, ci, i64, i64, i64, ci, cp]),
         "sw_plan_levels": (ci, [i64, i64]),
@@ -145,6 +146,17 @@ def sw_flop_count(n, levels):
 
 def sw_last_error():
     return lib().sw_last_error().decode()
+
+
+def sw_trace_gemm(M, N, K, lda, ldb, ldc, levels, schedule, workspace_bytes, overlap=1, odd_mode=SW_ODD_PAD, withhold=-1):
+    """The record of a launch-free run of sw_gemm_rect as a numpy int64 array (format: include/sw_gemm.h)."""
+    import numpy as np
+    args = (M, N, K, lda, ldb, ldc, levels, _sched(schedule), workspace_bytes, int(overlap), odd_mode, withhold)
+    words = _check(lib().sw_trace_gemm(*args, None, 0))
+    log = np.empty(max(words, 1), dtype=np.int64)
+    got = _check(lib().sw_trace_gemm(*args, log.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), words))
+    assert got == words
+    return log[:words]
 
 
 # ---- device calls ----------------------------------------------------------------------------------------------

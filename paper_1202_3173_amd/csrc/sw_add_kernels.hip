@@ -12,18 +12,9 @@
 namespace sw {
 namespace {
 
-#ifndef SW_ADD_NT_THREADS
-#define SW_ADD_NT_THREADS 256
-#endif
-#ifndef SW_ADD_ROWS
-#define SW_ADD_ROWS 2
-#endif
-#ifndef SW_ADD_POST_ROWS
-#define SW_ADD_POST_ROWS 2
-#endif
-constexpr int NT = SW_ADD_NT_THREADS;   // threads per block
-constexpr int ROWS = SW_ADD_ROWS;       // rows per thread (independent loads in flight)
-constexpr int POST_ROWS = SW_ADD_POST_ROWS;
+constexpr int NT = 256;                  // threads per block
+constexpr int ROWS = 2;                  // rows per thread (independent loads in flight)
+constexpr int POST_ROWS = 2;
 constexpr int PAD_ROWS = 8;              // rows per thread of the pad / crop copy
 
 // Every kernel below walks a LOGICAL grid (column chunks x row groups x matrices) with however many
@@ -48,20 +39,13 @@ template <> struct VecT<2> { typedef double __attribute__((ext_vector_type(2))) 
 template <int VEC>
 __device__ __forceinline__ typename VecT<VEC>::type ld(const double* p)
 {
-#ifndef SW_ADD_TEMPORAL   /* streaming data: nothing here is read again before it has left every cache */
+    // streaming data: nothing here is read again before it has left every cache
     return __builtin_nontemporal_load(reinterpret_cast<const typename VecT<VEC>::type*>(p));
-#else
-    return *reinterpret_cast<const typename VecT<VEC>::type*>(p);
-#endif
 }
 template <int VEC>
 __device__ __forceinline__ void st(double* p, typename VecT<VEC>::type v)
 {
-#ifndef SW_ADD_TEMPORAL
     __builtin_nontemporal_store(v, reinterpret_cast<typename VecT<VEC>::type*>(p));
-#else
-    *reinterpret_cast<typename VecT<VEC>::type*>(p) = v;
-#endif
 }
 
 // ---- BFS pre-additions ------------------------------------------------------------------------------------
@@ -444,7 +428,9 @@ inline LGrid grid_for(int64_t hr, int64_t hc, int vec, int rows, int64_t batch)
     return LGrid{(unsigned)((chunks + NT - 1) / NT), (unsigned)((hr + rows - 1) / rows), (unsigned)batch};
 }
 
-static int g_block_cap = 0;   // 0: one workgroup per logical block; else at most this many workgroups per launch
+// 0: one workgroup per logical block; else at most this many workgroups per launch.  Per host thread, so that
+// two threads inside the library at once do not change each other's launches.
+static thread_local int g_block_cap = 0;
 
 inline dim3 physical(const LGrid& lg)
 {
@@ -460,6 +446,8 @@ void set_add_block_cap(int cap) { g_block_cap = cap; }
 hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t hr, int64_t hc, Mat child, bool copies, hipStream_t s)
 {
     if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    if (Tracer* t = tracer())
+        return t->kernel(Tracer::K_PRE_ADD, s, {fp(parent, 2 * hr, 2 * hc, live)}, {fp(child, hr, hc, (copies ? 7 : 4) * live)});
     const bool v2 = even(hc) && mat_vec2(parent) && mat_vec2(child);
     const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                              \
@@ -474,6 +462,7 @@ hipError_t launch_pre_add(int side, Mat parent, int64_t live, int64_t hr, int64_
 hipError_t launch_post_add(Mat q, int64_t live, int64_t hr, int64_t hc, Mat parent, hipStream_t s)
 {
     if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    if (Tracer* t = tracer()) return t->kernel(Tracer::K_POST_ADD, s, {fp(q, hr, hc, 7 * live)}, {fp(parent, 2 * hr, 2 * hc, live)});
     const bool v2 = even(hc) && mat_vec2(parent) && mat_vec2(q);
     const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, POST_ROWS, live);
     if (v2)
@@ -488,6 +477,7 @@ hipError_t launch_post_add(Mat q, int64_t live, int64_t hr, int64_t hc, Mat pare
 hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t mr, int64_t mc, Mat child, hipStream_t s)
 {
     if (live == 0 || mr == 0 || mc == 0) return hipSuccess;
+    if (Tracer* t = tracer()) return t->kernel(Tracer::K_PRE_ADD2, s, {fp(parent, 4 * mr, 4 * mc, live)}, {fp(child, mr, mc, 49 * live)});
     const bool v2 = even(mc) && mat_vec2(parent) && mat_vec2(child);
     const LGrid lg = grid_for(mr, mc, v2 ? 2 : 1, 1, live);
 #define SW_LAUNCH(SIDE, VEC)                                                                               \
@@ -502,6 +492,7 @@ hipError_t launch_pre_add2(int side, Mat parent, int64_t live, int64_t mr, int64
 hipError_t launch_post_add2(Mat q, int64_t live, int64_t mr, int64_t mc, Mat parent, hipStream_t s)
 {
     if (live == 0 || mr == 0 || mc == 0) return hipSuccess;
+    if (Tracer* t = tracer()) return t->kernel(Tracer::K_POST_ADD2, s, {fp(q, mr, mc, 49 * live)}, {fp(parent, 4 * mr, 4 * mc, live)});
     const bool v2 = even(mc) && mat_vec2(parent) && mat_vec2(q);
     const LGrid lg = grid_for(mr, mc, v2 ? 2 : 1, 1, live);
     if (v2)
@@ -521,6 +512,7 @@ static EwOp make_op(Mat z, Mat x, Mat y, int sign)
 hipError_t launch_ew(Mat z, Mat x, Mat y, int sign, int64_t live, int64_t hr, int64_t hc, hipStream_t s)
 {
     if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    if (Tracer* t = tracer()) return t->kernel(Tracer::K_EW, s, {fp(x, hr, hc, live), fp(y, hr, hc, live)}, {fp(z, hr, hc, live)});
     const bool v2 = even(hc) && mat_vec2(z) && mat_vec2(x) && mat_vec2(y);
     const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, live);
     const EwOp op = make_op(z, x, y, sign);
@@ -533,6 +525,9 @@ hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1,
                       int64_t hr, int64_t hc, hipStream_t s)
 {
     if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    if (Tracer* t = tracer())
+        return t->kernel(Tracer::K_EW, s, {fp(x0, hr, hc, live), fp(y0, hr, hc, live), fp(x1, hr, hc, live), fp(y1, hr, hc, live)},
+                         {fp(z0, hr, hc, live), fp(z1, hr, hc, live)});
     const bool v2 = even(hc) && mat_vec2(z0) && mat_vec2(x0) && mat_vec2(y0) && mat_vec2(z1) && mat_vec2(x1) &&
                     mat_vec2(y1);
     const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, ROWS, 2 * live);
@@ -545,6 +540,10 @@ hipError_t launch_ew2(Mat z0, Mat x0, Mat y0, int sign0, Mat z1, Mat x1, Mat y1,
 hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int64_t live, int64_t hr, int64_t hc, hipStream_t s)
 {
     if (live == 0 || hr == 0 || hc == 0) return hipSuccess;
+    if (Tracer* t = tracer())
+        return t->kernel(Tracer::K_DFS_POST, s,
+                         {fp(x, hr, hc, live), fp(c11, hr, hc, live), fp(c12, hr, hc, live), fp(c21, hr, hc, live), fp(c22, hr, hc, live)},
+                         {fp(c12, hr, hc, live), fp(c21, hr, hc, live), fp(c22, hr, hc, live)});
     // the four quadrants share ld and stride by construction
     const bool v2 = even(hc) && mat_vec2(x) && mat_vec2(c11) && mat_vec2(c12) && mat_vec2(c21) && mat_vec2(c22);
     const LGrid lg = grid_for(hr, hc, v2 ? 2 : 1, 2, live);
@@ -561,6 +560,12 @@ hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int6
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s)
 {
     if (prows == 0 || pcols == 0) return hipSuccess;
+    if (Tracer* t = tracer()) {
+        const int64_t r = rows < prows ? rows : prows, c = cols < pcols ? cols : pcols;
+        const Footprint out{dst, prows, pcols, dst_ld, 1, 0};
+        if (r > 0 && c > 0) return t->kernel(Tracer::K_PAD_COPY, s, {Footprint{src, r, c, src_ld, 1, 0}}, {out});
+        return t->kernel(Tracer::K_PAD_COPY, s, {}, {out});
+    }
     const LGrid lg{(unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + PAD_ROWS - 1) / PAD_ROWS), 1u};
     hipLaunchKernelGGL(pad_copy_kernel, physical(lg), dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
                        (int)prows, (int)pcols, lg);

@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -32,13 +34,19 @@ int hip_fail(hipError_t e, const char* what)
 
 // ---- library state --------------------------------------------------------------------------------------------
 
+// Process-wide settings.  Every entry point reads them ONCE, on entry (current_opts, library_state); nothing
+// below the entry points looks at them, so a setter called from another thread affects later calls only.
 static void* g_ws = nullptr;
 static int64_t g_ws_bytes = 0;
 static hipStream_t g_stream = nullptr;
-static int g_odd_mode = SW_ODD_PAD;   // what to do when 2^levels does not divide n
-static int g_overlap = 1;             // 0: one stream.  > 0: additions and leaf products on separate streams (when the
-                                      // step order has a DFS step); the addition kernels beside the leaf products then
-                                      // run with a limited number of workgroups: 1 = sized to the work, k > 1 = k
+static std::atomic<int> g_odd_mode{SW_ODD_PAD};   // what to do when 2^levels does not divide n
+static std::atomic<int> g_overlap{1};             // 0: one stream.  > 0: additions and leaf products on separate streams (when
+                                                  // the step order has a DFS step); the addition kernels beside the leaf
+                                                  // products then run with a limited number of workgroups: 1 = sized to the
+                                                  // work, k > 1 = k
+static std::atomic<bool> g_prof_on{false};
+
+CallOpts current_opts() { return CallOpts{g_overlap.load(), g_odd_mode.load(), g_prof_on.load(), false}; }
 
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream)
 {
@@ -47,10 +55,18 @@ void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream)
     *stream = g_stream;
 }
 
+// ---- record-only runs ---------------------------------------------------------------------------------------------
+
+static thread_local Tracer* t_tracer = nullptr;
+static thread_local int64_t t_withhold = -1;   // see Exec::withhold; set by sw_trace_gemm only
+Tracer* tracer() { return t_tracer; }
+void set_tracer(Tracer* t) { t_tracer = t; }
+
 // ---- profiling ------------------------------------------------------------------------------------------------
 
 struct Profiler {
     struct Rec { hipEvent_t e0, e1; int cls; double work; };
+    std::mutex mu;              // records may come from several host threads
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t take()
@@ -63,22 +79,31 @@ struct Profiler {
 };
 
 static Profiler g_prof;
-static bool g_prof_on = false;
 
-Profiler* profiler() { return g_prof_on ? &g_prof : nullptr; }
+Profiler* profiler() { return g_prof_on.load() ? &g_prof : nullptr; }
 
-void prof_begin(Profiler* p, hipStream_t s, int cls, double work)
+// Brackets one launch (or a short run of launches on one stream) with two events.  The record is appended
+// only when both events have been recorded, so records of concurrent callers never interleave.
+void prof_begin(Profiler* p, hipStream_t s, int cls, double work, ProfMark* m)
 {
+    m->e0 = m->e1 = nullptr;
+    m->cls = cls;
+    m->work = work;
     if (!p) return;
-    Profiler::Rec r{p->take(), p->take(), cls, work};
-    if (r.e0) (void)hipEventRecord(r.e0, s);
-    p->recs.push_back(r);
+    {
+        std::lock_guard<std::mutex> g(p->mu);
+        m->e0 = p->take();
+        m->e1 = p->take();
+    }
+    if (m->e0) (void)hipEventRecord(m->e0, s);
 }
 
-void prof_end(Profiler* p, hipStream_t s)
+void prof_end(Profiler* p, hipStream_t s, const ProfMark* m)
 {
-    if (!p || p->recs.empty()) return;
-    if (p->recs.back().e1) (void)hipEventRecord(p->recs.back().e1, s);
+    if (!p) return;
+    if (m->e1) (void)hipEventRecord(m->e1, s);
+    std::lock_guard<std::mutex> g(p->mu);
+    p->recs.push_back(Profiler::Rec{m->e0, m->e1, m->cls, m->work});
 }
 
 // ---- schedule checks and the planner ------------------------------------------------------------------------------
@@ -117,11 +142,14 @@ static Dims floor_dims(Dims d, int levels)
     return Dims{d.m - d.m % q, d.n - d.n % q, d.k - d.k % q};
 }
 
-int64_t total_need(Dims d, int levels, const char* sched)
+int64_t total_need(Dims d, int levels, const char* sched) { return total_need(d, levels, sched, g_odd_mode.load()); }
+int plan(Dims d, int levels, int64_t budget, char* out) { return plan(d, levels, budget, out, g_odd_mode.load()); }
+
+int64_t total_need(Dims d, int levels, const char* sched, int odd_mode)
 {
     if (d.m == 0 || d.n == 0 || d.k == 0) return 0;
     // peeling: the recursion runs in place on the previous multiples of 2^levels, no copies
-    if (g_odd_mode == SW_ODD_PEEL) return ws_need_bytes(floor_dims(d, levels), sched, 1);
+    if (odd_mode == SW_ODD_PEEL) return ws_need_bytes(floor_dims(d, levels), sched, 1);
     const Dims p = padded_dims(d, levels);
     int64_t bytes = ws_need_bytes(p, sched, 1);
     if (p.m != d.m || p.n != d.n || p.k != d.k)
@@ -129,7 +157,7 @@ int64_t total_need(Dims d, int levels, const char* sched)
     return bytes;
 }
 
-int plan(Dims d, int levels, int64_t budget, char* out)
+int plan(Dims d, int levels, int64_t budget, char* out, int odd_mode)
 {
     // Enumerate all step orders.  Preference: most BFS steps (largest leaf batch per launch, fewest
     // launches), then least memory, which puts the DFS steps first (the Limited-Memory shape of Section 3.4).
@@ -144,7 +172,7 @@ int plan(Dims d, int levels, int64_t budget, char* out)
             nb += b;
         }
         cand[levels] = '\0';
-        const int64_t need = total_need(d, levels, cand);
+        const int64_t need = total_need(d, levels, cand, odd_mode);
         if (need > budget) continue;
         if (nb > best_b || (nb == best_b && need < best_need)) {
             best_b = nb;
@@ -155,7 +183,7 @@ int plan(Dims d, int levels, int64_t budget, char* out)
     if (best_b < 0) {
         set_error("no step order for %lld x %lld x %lld, levels = %d fits a workspace of %lld bytes (all-DFS needs %lld)",
                   (long long)d.m, (long long)d.n, (long long)d.k, levels, (long long)budget,
-                  (long long)total_need(d, levels, std::string((size_t)levels, 'D').c_str()));
+                  (long long)total_need(d, levels, std::string((size_t)levels, 'D').c_str(), odd_mode));
         return SW_ENOMEM;
     }
     return SW_OK;
@@ -192,52 +220,88 @@ struct Sched {
     struct Acc { uintptr_t lo, hi; uint64_t seq; uint8_t stream; bool write; };
     std::vector<Acc> live;
     hipError_t err = hipSuccess;
+    Tracer* tr = nullptr;                           // record-only run: events and waits are written down, not issued
 
-    // process-wide pool: two internal streams and the event rings (created once, never destroyed)
-    struct Pool { hipStream_t pre = nullptr, mm = nullptr; hipEvent_t ring[NSTREAM][RING]; hipEvent_t entry; bool ok = false; };
-    static Pool& pool()
+    // Two internal streams and the events of one product in flight on the host side.  A call takes a lane for
+    // its duration (from entry to return; the GPU work it enqueued may still run) and hands it back, so two
+    // host threads inside the library at once never share events, while consecutive calls of one thread reuse
+    // the same streams.  Lanes are created on demand and live until the process ends.
+    struct Lane { hipStream_t pre = nullptr, mm = nullptr; hipEvent_t ring[NSTREAM][RING]; hipEvent_t entry = nullptr; bool busy = false; };
+    Lane* lane = nullptr;
+
+    static std::mutex& lanes_mutex() { static std::mutex m; return m; }
+    static std::vector<Lane*>& lanes() { static std::vector<Lane*> v; return v; }
+
+    static Lane* take_lane()
     {
-        static Pool p;
-        if (!p.ok) {
-            bool good = hipStreamCreateWithFlags(&p.pre, hipStreamNonBlocking) == hipSuccess &&
-                        hipStreamCreateWithFlags(&p.mm, hipStreamNonBlocking) == hipSuccess &&
-                        hipEventCreateWithFlags(&p.entry, hipEventDisableTiming) == hipSuccess;
-            for (int s = 0; s < NSTREAM && good; ++s)
-                for (int i = 0; i < RING && good; ++i)
-                    good = hipEventCreateWithFlags(&p.ring[s][i], hipEventDisableTiming) == hipSuccess;
-            p.ok = good;
-        }
-        return p;
+        std::lock_guard<std::mutex> g(lanes_mutex());
+        for (Lane* l : lanes())
+            if (!l->busy) { l->busy = true; return l; }
+        Lane* l = new Lane;
+        bool good = hipStreamCreateWithFlags(&l->pre, hipStreamNonBlocking) == hipSuccess &&
+                    hipStreamCreateWithFlags(&l->mm, hipStreamNonBlocking) == hipSuccess &&
+                    hipEventCreateWithFlags(&l->entry, hipEventDisableTiming) == hipSuccess;
+        for (int s = 0; s < NSTREAM && good; ++s)
+            for (int i = 0; i < RING && good; ++i)
+                good = hipEventCreateWithFlags(&l->ring[s][i], hipEventDisableTiming) == hipSuccess;
+        if (!good) { (void)hipGetLastError(); delete l; return nullptr; }   // no streams or events to be had (what was created stays)
+        l->busy = true;
+        lanes().push_back(l);
+        return l;
+    }
+    static void give_lane(Lane* l)
+    {
+        std::lock_guard<std::mutex> g(lanes_mutex());
+        l->busy = false;
     }
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
 
+    // slot -1 is the entry event (recorded on the caller's stream), slot i >= 0 is ring[s][i]
+    void ev_record(int s, int slot)
+    {
+        if (tr) { tr->record(s, slot); return; }
+        note(hipEventRecord(slot < 0 ? lane->entry : lane->ring[s][slot], st[s]));
+    }
+    void ev_wait(int c, int s, int slot)
+    {
+        if (tr) { tr->wait(c, s, slot); return; }
+        note(hipStreamWaitEvent(st[c], slot < 0 ? lane->entry : lane->ring[s][slot], 0));
+    }
+
     // the caller's stream carries the post-additions; the two others first wait for what the caller queued
     void start(hipStream_t caller, bool want_multi)
     {
+        tr = tracer();
+        if (tr) caller = (hipStream_t)(uintptr_t)1;
         st[S_POST] = st[S_PRE] = st[S_MM] = caller;
         multi = false;
         if (!want_multi) return;
-        // under stream capture everything stays on the capturing stream: the graph then holds the kernels in
-        // program order (forking a capture over the library's own streams is not attempted)
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(caller, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
-        if (cap != hipStreamCaptureStatusNone) return;
-        Pool& p = pool();
-        if (!p.ok) return;                          // no streams or events to be had: stay on one stream
+        if (tr) {
+            st[S_PRE] = (hipStream_t)(uintptr_t)2;
+            st[S_MM] = (hipStream_t)(uintptr_t)3;
+        } else {
+            // under stream capture everything stays on the capturing stream: the graph then holds the kernels in
+            // program order (forking a capture over the library's own streams is not attempted)
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(caller, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+            if (cap != hipStreamCaptureStatusNone) return;
+            lane = take_lane();
+            if (!lane) return;                          // stay on one stream
+            st[S_PRE] = lane->pre;
+            st[S_MM] = lane->mm;
+        }
         multi = true;
-        st[S_PRE] = p.pre;
-        st[S_MM] = p.mm;
-        note(hipEventRecord(p.entry, caller));
-        note(hipStreamWaitEvent(p.pre, p.entry, 0));
-        note(hipStreamWaitEvent(p.mm, p.entry, 0));
+        ev_record(S_POST, -1);
+        ev_wait(S_PRE, S_POST, -1);
+        ev_wait(S_MM, S_POST, -1);
     }
 
     void wait_for(int c, int s, uint64_t n)          // stream c waits for kernel number n (1-based) of stream s
     {
         if (c == s || waited[c][s] >= n) return;
         const uint64_t use = (seq[s] - n < (uint64_t)RING) ? n : seq[s];   // its own event, or a later one
-        note(hipStreamWaitEvent(st[c], pool().ring[s][(use - 1) % RING], 0));
+        ev_wait(c, s, (int)((use - 1) % RING));
         waited[c][s] = use;
     }
 
@@ -260,7 +324,7 @@ struct Sched {
     {
         if (!multi) return;
         ++seq[c];
-        note(hipEventRecord(pool().ring[c][(seq[c] - 1) % RING], st[c]));
+        ev_record(c, (int)((seq[c] - 1) % RING));
         for (int i = 0; i < nr; ++i) live.push_back(Acc{reads[i].lo, reads[i].hi, seq[c], (uint8_t)c, false});
         for (int i = 0; i < nw; ++i) live.push_back(Acc{writes[i].lo, writes[i].hi, seq[c], (uint8_t)c, true});
         if (live.size() >= 512) prune();
@@ -285,16 +349,22 @@ struct Sched {
         for (size_t i = 0; i < live.size(); ++i)
             if (!settled(live[i])) live[k++] = live[i];
         live.resize(k);
-        if (live.size() >= 384) { join_all(); live.clear(); }
+        if (live.size() >= 384) {
+            if (tr) tr->joined((int64_t)live.size());
+            join_all();
+            live.clear();
+        }
     }
 
     // the caller's stream ends up ordered after everything
     void finish()
     {
-        if (!multi) return;
-        for (int s = 1; s < NSTREAM; ++s)
-            if (seq[s] > 0) wait_for(S_POST, s, seq[s]);
+        if (multi)
+            for (int s = 1; s < NSTREAM; ++s)
+                if (seq[s] > 0) wait_for(S_POST, s, seq[s]);
+        if (lane) { give_lane(lane); lane = nullptr; }
     }
+    ~Sched() { if (lane) give_lane(lane); }
 };
 
 // ---- the executor ----------------------------------------------------------------------------------------------
@@ -314,12 +384,21 @@ struct Exec {
     bool bg = false;              // the operations being issued are the leaf-side ones of a double-buffered step
     Profiler* prof;
     hipError_t err = hipSuccess;
+    int64_t declared = 0;         // ranges declared to the dependency tracker so far
+    int64_t withhold = -1;        // record-only runs: the number of ONE declared range to keep from the tracker (a
+                                  // planted mistake, which the checker of the record must then find); -1: none
 
     double* take(int64_t elems)
     {
         double* p = reinterpret_cast<double*>(ws + used);
+        if (sc.tr) sc.tr->take(used, elems * (int64_t)sizeof(double));
         used += elems * (int64_t)sizeof(double);
         return p;
+    }
+    void pop_to(int64_t mark)
+    {
+        used = mark;
+        if (sc.tr) sc.tr->pop(mark);
     }
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
@@ -347,12 +426,17 @@ struct Exec {
     void op(int s, int cls, double work, std::initializer_list<Range> reads, std::initializer_list<Range> writes, F&& launch)
     {
         if (err != hipSuccess) return;
-        sc.acquire(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
+        Range rd[8], wr[8];
+        int nr = 0, nw = 0;
+        for (const Range& r : reads) if (declared++ != withhold) rd[nr++] = r;
+        for (const Range& r : writes) if (declared++ != withhold) wr[nw++] = r;
+        sc.acquire(s, rd, nr, wr, nw);
         if (sc.multi) set_add_block_cap(bg ? cap_bg : 0);   // kernels on the critical path get the whole machine
-        prof_begin(prof, sc.st[s], cls, work);
+        ProfMark pm_;
+        prof_begin(prof, sc.st[s], cls, work, &pm_);
         note(launch(sc.st[s]));
-        prof_end(prof, sc.st[s]);
-        sc.release(s, reads.begin(), (int)reads.size(), writes.begin(), (int)writes.size());
+        prof_end(prof, sc.st[s], &pm_);
+        sc.release(s, rd, nr, wr, nw);
         note(sc.err);
     }
 
@@ -398,7 +482,7 @@ struct Exec {
         const int64_t e4T = ws_mat_elems(q.m, q.k), e4S = ws_mat_elems(q.k, q.n), e4Q = ws_mat_elems(q.m, q.n);
         // the step whose children are the leaves: with two sets of buffers, consecutive launches alternate
         if (dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels && (flip++ & 1))
-            used += (fused ? 49 * live * (e4T + e4S + e4Q) : 7 * live * (eT + eS + eQ)) * (int64_t)sizeof(double);
+            used += (fused ? 49 * live * (e4T + e4S + e4Q) : 7 * live * (eT + eS + eQ)) * (int64_t)sizeof(double);   // skip the first set
         const bool was_bg = bg;
         bg = dbl && sched[level] == 'B' && level + (fused ? 2 : 1) == levels;
         if (bg)
@@ -480,7 +564,7 @@ struct Exec {
             ew(S_POST, C11, XQ, C11, +1, live, h.m, h.n);              // C11 = Q0 + Q1
         }
         bg = was_bg;
-        used = mark;
+        pop_to(mark);
     }
 };
 
@@ -494,12 +578,18 @@ bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn)
 int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                    int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream)
 {
+    return gemm_rect_impl(d, A, lda, B, ldb, C, ldc, levels, schedule, ws, ws_bytes, stream, current_opts());
+}
+
+int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                   int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream, const CallOpts& opts)
+{
     const int64_t dmin = d.m < d.n ? (d.m < d.k ? d.m : d.k) : (d.n < d.k ? d.n : d.k);
     const int64_t dmax = d.m > d.n ? (d.m > d.k ? d.m : d.k) : (d.n > d.k ? d.n : d.k);
     if (levels < 0) {
         // depth left open: the cost model's choice for this workspace, step order by the planner
         if (dmin < 0 || dmax > 200000) { set_error("bad shape: %lld x %lld x %lld", (long long)d.m, (long long)d.n, (long long)d.k); return SW_EINVAL; }
-        levels = plan_levels(dmin, ws ? ws_bytes : 0);
+        levels = plan_levels(dmin, (ws || opts.check_only) ? ws_bytes : 0);
         schedule = nullptr;
     }
     int rc = check_shape(dmin, levels);
@@ -509,6 +599,10 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
     if (d.k == 0) { set_error("empty inner dimension"); return SW_EINVAL; }
     if (!A || !B || !C) { set_error("NULL matrix pointer"); return SW_EINVAL; }
     if (lda < d.k || ldb < d.n || ldc < d.n) { set_error("leading dimension smaller than the row length"); return SW_EINVAL; }
+    if (!gemm_pitches_ok(lda, ldb)) {
+        set_error("leading dimension too large for the product kernel's 32-bit offsets (lda <= 4227329, ldb <= 35791385)");
+        return SW_EINVAL;
+    }
     const int64_t spanA = (d.m - 1) * lda + d.k, spanB = (d.k - 1) * ldb + d.n, spanC = (d.m - 1) * ldc + d.n;
     if (overlaps(C, spanC, A, spanA) || overlaps(C, spanC, B, spanB)) {
         set_error("C overlaps A or B");
@@ -516,15 +610,21 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
     }
     char chosen[SW_MAX_LEVELS + 1];
     if (!schedule || !*schedule) {
-        rc = plan(d, levels, ws ? ws_bytes : 0, chosen);
+        rc = plan(d, levels, (ws || opts.check_only) ? ws_bytes : 0, chosen, opts.odd_mode);
         if (rc != SW_OK) return rc;
         schedule = chosen;
     } else if (!schedule_ok(schedule, levels)) {
         set_error("schedule \"%s\" must be %d characters of B or D", schedule, levels);
         return SW_EINVAL;
     }
-    const int64_t need = total_need(d, levels, schedule);
-    if (need > 0) {
+    const int64_t need = total_need(d, levels, schedule, opts.odd_mode);
+    if (need > 0 && opts.check_only) {
+        if (ws_bytes < need) {
+            set_error("workspace of %lld bytes is too small: %lld x %lld x %lld, schedule %s needs %lld", (long long)ws_bytes,
+                      (long long)d.m, (long long)d.n, (long long)d.k, schedule, (long long)need);
+            return SW_ENOMEM;
+        }
+    } else if (need > 0) {
         if (!ws || ws_bytes < need) {
             set_error("workspace of %lld bytes is too small: %lld x %lld x %lld, schedule %s needs %lld", (long long)(ws ? ws_bytes : 0),
                       (long long)d.m, (long long)d.n, (long long)d.k, schedule, (long long)need);
@@ -537,6 +637,7 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
             return SW_EINVAL;
         }
     }
+    if (opts.check_only) return SW_OK;
 
     Exec ex;
     ex.ws = (char*)ws;
@@ -544,20 +645,21 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
     ex.sched = schedule;
     ex.levels = levels;
     const Dims lead = floor_dims(d, levels);
-    const bool peel = g_odd_mode == SW_ODD_PEEL && (lead.m != d.m || lead.n != d.n || lead.k != d.k);
+    const bool peel = opts.odd_mode == SW_ODD_PEEL && (lead.m != d.m || lead.n != d.n || lead.k != d.k);
     const Dims rec = peel ? lead : padded_dims(d, levels);
     {
         // spend what the workspace has beyond the minimum: first on a second set of the buffers next to the
         // leaves (so that additions and leaf products of consecutive launches overlap), then on the rich form
         // of the deepest DFS steps
         const int64_t fixed = need - ws_need_bytes(rec, schedule, 1);
-        choose_options(rec, levels, schedule, ws_bytes - fixed, g_overlap != 0, &ex.rich, &ex.dbl);
+        choose_options(rec, levels, schedule, ws_bytes - fixed, opts.overlap != 0, &ex.rich, &ex.dbl);
     }
-    ex.prof = profiler();
+    ex.prof = (opts.profile && !tracer()) ? profiler() : nullptr;
+    ex.withhold = t_withhold;
     // with BFS steps only the kernels form one chain: nothing could overlap, so one stream it is
-    ex.sc.start(stream, g_overlap != 0 && levels > 0 && strchr(schedule, 'D') != nullptr);
+    ex.sc.start(stream, opts.overlap != 0 && levels > 0 && strchr(schedule, 'D') != nullptr);
     set_add_block_cap(0);
-    ex.cap_fixed = g_overlap;
+    ex.cap_fixed = opts.overlap;
 
     Mat a{const_cast<double*>(A), lda, 0}, b{const_cast<double*>(B), ldb, 0}, c{C, ldc, 0};
     if (peel) {
@@ -642,6 +744,25 @@ int sw_gemm_rect(int64_t M, int64_t N, int64_t K, const double* A, int64_t lda, 
     return gemm_rect_impl(Dims{M, N, K}, A, lda, B, ldb, C, ldc, levels, schedule, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+int64_t sw_trace_gemm(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int levels, const char* schedule,
+                      int64_t workspace_bytes, int overlap, int odd_mode, int64_t withhold, int64_t* log, int64_t log_words)
+{
+    if (workspace_bytes < 0 || M < 0 || N < 0 || K < 0 || log_words < 0 || overlap < 0) { set_error("negative argument"); return SW_EINVAL; }
+    if (odd_mode != SW_ODD_PAD && odd_mode != SW_ODD_PEEL) { set_error("unknown mode %d", odd_mode); return SW_EINVAL; }
+    // synthetic operand addresses, 2^40 bytes apart (no matrix the library accepts is that large)
+    const uintptr_t T = (uintptr_t)1 << 40;
+    Tracer t;
+    t.out = log;
+    t.cap = log ? log_words : 0;
+    set_tracer(&t);
+    t_withhold = withhold;
+    const int rc = gemm_rect_impl(Dims{M, N, K}, (const double*)(1 * T), lda, (const double*)(2 * T), ldb, (double*)(3 * T), ldc, levels,
+                                  schedule, (void*)(4 * T), workspace_bytes, nullptr, CallOpts{overlap, odd_mode, false, false});
+    set_tracer(nullptr);
+    t_withhold = -1;
+    return rc != SW_OK ? rc : t.words;
+}
+
 int64_t sw_plan_memory_rect(int64_t M, int64_t N, int64_t K, int levels, const char* schedule)
 {
     if (M < 0 || N < 0 || K < 0) { set_error("negative dimension"); return SW_EINVAL; }
@@ -703,7 +824,8 @@ int sw_gemm_scaled(int64_t n, const double* A, const double* B, double* C, int l
     auto note = [&](hipError_t x) { if (err == hipSuccess && x != hipSuccess) err = x; };
     const bool outside = scaling & SW_SCALE_OUTSIDE, inside = scaling & SW_SCALE_INSIDE;
     Profiler* prof = profiler();
-    prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * (outside ? 2.0 : 0.0) + 8.0 * n * n * (inside ? 2.0 : 0.0) + 8.0 * n * n * 4.0);
+    ProfMark pm_;
+    prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * (outside ? 2.0 : 0.0) + 8.0 * n * n * (inside ? 2.0 : 0.0) + 8.0 * n * n * 4.0, &pm_);
     if (outside) {
         note(launch_absmax_rows(A, n, n, nullptr, ma, st));            // max_j |A_ij|
         note(launch_outside_scale(ma, n, d1, st));
@@ -717,17 +839,18 @@ int sw_gemm_scaled(int64_t n, const double* A, const double* B, double* C, int l
     }
     note(launch_scale_copy(A, n, n, outside ? d1 : nullptr, inside ? d2 : nullptr, As, ld, st));    // D1 A D2
     note(launch_scale_copy(B, n, n, inside ? d2i : nullptr, outside ? d3 : nullptr, Bs, ld, st));   // D2^-1 B D3
-    prof_end(prof, st);
+    prof_end(prof, st, &pm_);
     if (err != hipSuccess) return hip_fail(err, "scaling kernels");
     rc = gemm_impl(n, As, ld, Bs, ld, C, n, levels, schedule, w + extra, g_ws_bytes - extra, st);
     if (rc != SW_OK) return rc;
     if (outside) {
         // C = D1^-1 C' D3^-1: the reciprocals of powers of two are formed exactly
-        prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * 2.0);
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_SCALE, 8.0 * n * n * 2.0, &pm_);
         note(launch_outside_scale(d1, n, ma, st));     // 2^-e(2^-k) = 2^k: reuses the exponent kernel to invert
         note(launch_outside_scale(d3, n, mb, st));
         note(launch_scale_copy(C, n, n, ma, mb, C, n, st));
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
         if (err != hipSuccess) return hip_fail(err, "unscaling kernels");
     }
     return SW_OK;
@@ -900,6 +1023,10 @@ int sw_leaf_gemm(int64_t m, int64_t batch, const double* A, int64_t lda, int64_t
         set_error("sw_leaf_gemm: bad argument");
         return SW_EINVAL;
     }
+    if (!gemm_pitches_ok(lda, ldb)) {
+        set_error("sw_leaf_gemm: leading dimension too large for the kernel's 32-bit offsets (lda <= 4227329, ldb <= 35791385)");
+        return SW_EINVAL;
+    }
     hipError_t e = launch_leaf_gemm(m, batch, Mat{const_cast<double*>(A), lda, stride_a},
                                     Mat{const_cast<double*>(B), ldb, stride_b}, Mat{C, ldc, stride_c},
                                     (hipStream_t)hip_stream);
@@ -912,6 +1039,10 @@ int sw_gemm_classical(int64_t M, int64_t N, int64_t K, const double* A, int64_t 
     if (M < 0 || N < 0 || K < 0 || M > 200000 || N > 200000 || K > 200000 || lda < K || ldb < N || ldc < N ||
         ((M > 0 && N > 0) && (!C || (K > 0 && (!A || !B))))) {
         set_error("sw_gemm_classical: bad argument");
+        return SW_EINVAL;
+    }
+    if (!gemm_pitches_ok(lda, ldb)) {
+        set_error("sw_gemm_classical: leading dimension too large for the kernel's 32-bit offsets (lda <= 4227329, ldb <= 35791385)");
         return SW_EINVAL;
     }
     if (M == 0 || N == 0) return SW_OK;

@@ -276,9 +276,10 @@ struct Walk {
     template <class F> void op(int cls, double work, F&& launch)
     {
         if (err != hipSuccess) return;
-        prof_begin(prof, st, cls, work);
+        ProfMark pm_;
+        prof_begin(prof, st, cls, work, &pm_);
         note(launch());
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
     }
     static int nonzero(const int8_t* c, int n) { int k = 0; for (int i = 0; i < n; ++i) k += c[i] != 0; return k; }
 

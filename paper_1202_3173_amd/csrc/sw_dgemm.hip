@@ -205,31 +205,35 @@ struct Dgemm {
     Mat blockA(int64_t i0, int64_t rows, int64_t k0, int64_t kc)
     {
         if (!ta) return Mat{const_cast<double*>(A) + i0 * lda + k0, lda, 0, false};
-        prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * rows * kc);
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * rows * kc, &pm_);
         note(launch_transpose(A + k0 * lda + i0, lda, kc, rows, TA, lda_t, st));
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
         return Mat{TA, lda_t, 0, lda_t > kc};
     }
     // op(B)[k0 .. k0+kc, j0 .. j0+cols)  (kc <= s.k, cols <= s.n)
     Mat blockB(int64_t k0, int64_t kc, int64_t j0, int64_t cols)
     {
         if (!tb) return Mat{const_cast<double*>(B) + k0 * ldb + j0, ldb, 0, false};
-        prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * kc * cols);
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_BLAS, 16.0 * kc * cols, &pm_);
         note(launch_transpose(B + j0 * ldb + k0, ldb, cols, kc, TB, ldb_t, st));
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
         return Mat{TB, ldb_t, 0, ldb_t > cols};
     }
     void fold(int64_t i0, int64_t rows, int64_t j0, int64_t cols, double b)
     {
-        prof_begin(prof, st, SW_CLASS_BLAS, 8.0 * rows * cols * (b != 0.0 ? 3.0 : 2.0));
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_BLAS, 8.0 * rows * cols * (b != 0.0 ? 3.0 : 2.0), &pm_);
         note(launch_axpby(C + i0 * ldc + j0, ldc, P, ldp, rows, cols, alpha, b, st));
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
     }
     void classical(int64_t rows, int64_t cols, int64_t kc, Mat a, Mat b, Mat c, bool accumulate)
     {
-        prof_begin(prof, st, SW_CLASS_PEEL, 2.0 * rows * cols * kc);
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_PEEL, 2.0 * rows * cols * kc, &pm_);
         note(launch_gemm(rows, cols, kc, 1, a, b, c, accumulate, st));
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
     }
 
     // an s.m x s.n block of C through the recursion, one inner slice of s.k after the other
@@ -397,14 +401,20 @@ int sw_dgemm(int transa, int transb, int64_t M, int64_t N, int64_t K, double alp
     Profiler* prof = profiler();
     if (K == 0 || alpha == 0.0) {
         // nothing to multiply: C <- beta * C, the operands are not read
-        prof_begin(prof, st, SW_CLASS_BLAS, 8.0 * M * N * 2.0);
+        ProfMark pm_;
+        prof_begin(prof, st, SW_CLASS_BLAS, 8.0 * M * N * 2.0, &pm_);
         hipError_t e = launch_axpby(C, ldc, nullptr, 0, M, N, 0.0, beta, st);
-        prof_end(prof, st);
+        prof_end(prof, st, &pm_);
         return e == hipSuccess ? SW_OK : hip_fail(e, "scaling kernel");
     }
     const int64_t arows = ta ? K : M, acols = ta ? M : K, brows = tb ? N : K, bcols = tb ? K : N;
     if (!A || !B) { set_error("NULL matrix pointer"); return SW_EINVAL; }
     if (lda < acols || ldb < bcols) { set_error("leading dimension smaller than the row length"); return SW_EINVAL; }
+    // operands that are not transposed are read by the product kernel as views of the caller's matrices
+    if (!gemm_pitches_ok(ta ? 0 : lda, tb ? 0 : ldb)) {
+        set_error("leading dimension too large for the product kernel's 32-bit offsets (lda <= 4227329, ldb <= 35791385)");
+        return SW_EINVAL;
+    }
     const int64_t spanA = (arows - 1) * lda + acols, spanB = (brows - 1) * ldb + bcols, spanC = (M - 1) * ldc + N;
     if (overlaps(C, spanC, A, spanA) || overlaps(C, spanC, B, spanB)) { set_error("C overlaps A or B"); return SW_EINVAL; }
     if (ws && ((uintptr_t)ws & 255u)) { set_error("workspace must be 256-byte aligned"); return SW_EINVAL; }

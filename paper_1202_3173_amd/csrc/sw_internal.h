@@ -4,6 +4,8 @@
 
 #include <stdint.h>
 
+#include <initializer_list>
+
 #include <hip/hip_runtime.h>
 
 #include "sw_gemm.h"
@@ -115,10 +117,22 @@ int check_shape(int64_t n, int levels);                // SW_OK or SW_EINVAL wit
 bool overlaps(const double* p, int64_t pn, const double* q, int64_t qn);   // element ranges [p, p+pn) and [q, q+qn)
 void library_state(void** ws, int64_t* ws_bytes, hipStream_t* stream);     // what sw_set_workspace / sw_set_stream left
 
+// The process-wide settings (sw_set_overlap, sw_set_odd_mode, sw_profile_enable) as one call sees them: an
+// entry point reads them once and hands them down; nothing below looks at the globals again.
+struct CallOpts {
+    int overlap;     // 0: one stream; 1: three streams, leaf-side additions sized to their work; k > 1: capped at k
+    int odd_mode;    // SW_ODD_PAD or SW_ODD_PEEL
+    bool profile;    // bracket every launch with events
+    bool check_only; // stop after the argument checks (the workspace pointer is not looked at, only its size)
+};
+CallOpts current_opts();
+
 // workspace bytes of the Strassen-Winograd product for this step order (with the padded copies, if any)
-int64_t total_need(Dims d, int levels, const char* sched);
+int64_t total_need(Dims d, int levels, const char* sched, int odd_mode);
+int64_t total_need(Dims d, int levels, const char* sched);                 // odd sizes as sw_set_odd_mode says now
 inline int64_t total_need(int64_t n, int levels, const char* sched) { return total_need(Dims{n, n, n}, levels, sched); }
 // the planner: most BFS steps that fit `budget`, then least memory; writes levels + 1 characters
+int plan(Dims d, int levels, int64_t budget, char* out, int odd_mode);
 int plan(Dims d, int levels, int64_t budget, char* out);
 inline int plan(int64_t n, int levels, int64_t budget, char* out) { return plan(Dims{n, n, n}, levels, budget, out); }
 // the depth with the least modelled time among those some step order fits into `budget` bytes (0 < n <= 200000)
@@ -130,13 +144,17 @@ int gemm_impl(int64_t n, const double* A, int64_t lda, const double* B, int64_t 
 // not divide are zero-padded into workspace copies
 int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                    int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream);
+// ... with the settings given instead of read from the process-wide ones
+int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                   int levels, const char* schedule, void* ws, int64_t ws_bytes, hipStream_t stream, const CallOpts& opts);
 
 // ---- profiling record (sw_profile_enable / sw_profile_read) ---------------------------------------------------
 
 struct Profiler;
+struct ProfMark { hipEvent_t e0, e1; int cls; double work; };   // one bracket, owned by the caller between begin and end
 Profiler* profiler();                                  // nullptr when profiling is off
-void prof_begin(Profiler*, hipStream_t, int cls, double work);
-void prof_end(Profiler*, hipStream_t);
+void prof_begin(Profiler*, hipStream_t, int cls, double work, ProfMark*);
+void prof_end(Profiler*, hipStream_t, const ProfMark*);
 
 // ---- a batch of equally shaped matrices: matrix b starts at p + b * stride, rows ld apart ----------------------
 
@@ -163,7 +181,39 @@ inline Mat ws_mat(double* p, int64_t h) { return ws_mat(p, h, h); }
 
 // At most `cap` workgroups per launch of an addition kernel (0: one per logical block).  With a cap the kernels
 // become persistent streaming kernels that occupy little of each CU, for running beside the leaf products.
+// The cap belongs to the calling host thread: launches of other threads are not affected.
 void set_add_block_cap(int cap);
+
+// ---- record-only runs (sw_trace_gemm) ---------------------------------------------------------------------------
+//
+// While a Tracer is installed on the calling thread nothing is launched and no HIP call is made: every launcher
+// below writes down what its kernel WOULD touch, from its own arguments (not from what the executor declared
+// to its dependency tracker), and the executor's event records and stream waits are written down in their
+// place.  A checker can then rebuild happens-before and look for unordered conflicting accesses.
+struct Footprint { const void* p; int64_t rows, cols, ld, count, stride; };   // `count` matrices of rows x cols doubles
+struct Tracer {
+    enum { KERNEL = 1, RECORD = 2, WAIT = 3, TAKE = 4, POP = 5, JOINED = 6 };
+    enum { K_PRE_ADD = 0, K_POST_ADD, K_PRE_ADD2, K_POST_ADD2, K_EW, K_DFS_POST, K_PAD_COPY, K_GEMM };
+    int64_t* out = nullptr;      // caller's buffer
+    int64_t cap = 0, words = 0;  // its capacity; words produced so far (may exceed cap: then only counted)
+    void put(int64_t v) { if (words < cap) out[words] = v; ++words; }
+    static int stream_id(hipStream_t s) { return (int)(uintptr_t)s - 1; }     // trace streams are the handles 1, 2, 3
+    hipError_t kernel(int kid, hipStream_t s, std::initializer_list<Footprint> reads, std::initializer_list<Footprint> writes)
+    {
+        put(KERNEL); put(stream_id(s)); put(kid); put((int64_t)reads.size()); put((int64_t)writes.size());
+        for (const auto* l : {&reads, &writes})
+            for (const Footprint& f : *l) { put((int64_t)(uintptr_t)f.p); put(f.rows); put(f.cols); put(f.ld); put(f.count); put(f.stride); }
+        return hipSuccess;
+    }
+    void record(int stream, int slot) { put(RECORD); put(stream); put(slot); }
+    void wait(int stream, int ev_stream, int slot) { put(WAIT); put(stream); put(ev_stream); put(slot); }
+    void take(int64_t offset, int64_t bytes) { put(TAKE); put(offset); put(bytes); }
+    void pop(int64_t offset) { put(POP); put(offset); }
+    void joined(int64_t tracked) { put(JOINED); put(tracked); }
+};
+Tracer* tracer();                 // the calling thread's tracer, nullptr outside sw_trace_gemm
+void set_tracer(Tracer*);
+inline Footprint fp(const Mat& m, int64_t rows, int64_t cols, int64_t count = 1) { return Footprint{m.p, rows, cols, m.ld, count, m.stride}; }
 
 // All addition kernels work on batches of hr x hc matrices (rows x columns); the square forms take h for both.
 // BFS pre-additions, Appendix A columns 1 (side 0, T from A) and 2 (side 1, S from B).
@@ -207,6 +257,9 @@ hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int6
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s);
 // Batched classical product on the fp64 matrix cores: C_b = A_b * B_b, all m x m.
 hipError_t launch_leaf_gemm(int64_t m, int64_t batch, Mat a, Mat b, Mat c, hipStream_t s);
+// Leading dimensions the kernel can address (its per-lane byte offsets are 32 bit): lda <= 4 227 329 and
+// ldb <= 35 791 385 doubles.  launch_gemm returns hipErrorInvalidValue beyond; entry points check first.
+bool gemm_pitches_ok(int64_t lda, int64_t ldb);
 // The same kernel on general shapes: C_b (M x N) = or += A_b (M x K) * B_b (K x N).
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, Mat a, Mat b, Mat c, bool accumulate,
                        hipStream_t s);

@@ -288,13 +288,25 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 }  // namespace
 
+// The kernel addresses a tile's operands as "uniform 64-bit panel base + 32-bit BYTE offset per lane": a lane
+// reaches up to 127 rows of A (plus 15 more doubles along the row) and 15 rows of B (plus 127 doubles) from
+// the base, so (127 lda + 16) * 8 and (15 ldb + 128) * 8 must stay below 2^32.
+bool gemm_pitches_ok(int64_t lda, int64_t ldb)
+{
+    const int64_t lim = (int64_t)1 << 32;
+    return lda >= 0 && ldb >= 0 && lda < lim && ldb < lim && (127 * lda + 16) * 8 < lim && (15 * ldb + 128) * 8 < lim;
+}
+
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, Mat a, Mat b, Mat c, bool accumulate,
                        hipStream_t s)
 {
     if (M == 0 || N == 0 || batch == 0) return hipSuccess;
     if (K == 0) return accumulate ? hipSuccess : hipErrorInvalidValue;   // callers never ask for an empty sum
-    // per-thread offsets inside one 128-row panel / 16-row slab are 32-bit element counts
-    if (128 * a.ld >= (int64_t)1 << 31 || 16 * b.ld >= (int64_t)1 << 31) return hipErrorInvalidValue;
+    if (!gemm_pitches_ok(a.ld, b.ld)) return hipErrorInvalidValue;
+    if (Tracer* t = tracer()) {
+        if (accumulate) return t->kernel(Tracer::K_GEMM, s, {fp(a, M, K, batch), fp(b, K, N, batch), fp(c, M, N, batch)}, {fp(c, M, N, batch)});
+        return t->kernel(Tracer::K_GEMM, s, {fp(a, M, K, batch), fp(b, K, N, batch)}, {fp(c, M, N, batch)});
+    }
     GemmArgs g;
     g.A = a.p; g.B = b.p; g.C = c.p;
     g.lda = a.ld; g.ldb = b.ld; g.ldc = c.ld;

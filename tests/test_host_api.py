@@ -57,7 +57,6 @@ def test_plan_memory_structure():
         if ld >= 256 and ld % 256 == 0:
             ld += 16
         return (ld * h + 31) // 32 * 32
-    import sw_bilinear
     assert sw.sw_plan_memory(256, 1, "B") == 21 * elems(128) * 8
     assert sw.sw_plan_memory(256, 1, "D") == 2 * elems(128) * 8
     assert sw.sw_plan_memory(1024, 2, "DB") == (2 * elems(512) + 21 * elems(256)) * 8
@@ -104,7 +103,6 @@ def test_plan_workspace_spends_extra_memory_on_the_deepest_dfs_steps():
         if ld >= 256 and ld % 256 == 0:
             ld += 16
         return (ld * h + 31) // 32 * 32
-    import sw_bilinear
     n, L, s = 1024, 3, "DDD"
     lean = sw.sw_plan_memory(n, L, s)
     assert lean == (2 * elems(512) + 2 * elems(256) + 2 * elems(128)) * 8
@@ -170,12 +168,12 @@ def test_argument_errors_without_gpu():
 
 def test_bilinear_memory_and_flop_counts(oracle):
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import sw_bilinear
 
     def ws_mat_elems(h):     # the documented workspace rule: pitch a multiple of 16, never of 256; slots of 32
         ld = (h + 15) // 16 * 16
         ld += 16 if ld % 256 == 0 else 0
         return (ld * h + 31) // 32 * 32
-    import sw_bilinear
     for scheme, q, oid in ((sw.SW_SCHEME_STRASSEN, 7, 0), (sw.SW_SCHEME_CLASSICAL, 8, 1)):
         n, levels = 1024, 3
         # BFS step: 3q half-size buffers per parent, the parents multiply by q; DFS step: 3 per parent
@@ -247,3 +245,30 @@ def test_rectangular_memory_formula():
     assert sw.sw_plan_memory_rect(100, 70, 33, 3, "DDD") == base + 8 * (elems(104, 40) + elems(40, 72) + elems(104, 72))
     with pytest.raises(sw.SwError):
         sw.sw_plan_memory_rect(64, 64, 3, 2, "BB")
+
+
+def test_leading_dimensions_beyond_the_product_kernels_reach_are_refused():
+    """The product kernel addresses a tile with 32-bit byte offsets per lane (127 rows of A, 15 rows of B from a
+    64-bit base): leading dimensions that would wrap them are an argument error before anything is launched.
+    No device memory is touched: the pointers are made up and never dereferenced."""
+    import ctypes
+    L = sw.lib()
+    p = lambda k: ctypes.c_void_p(k << 40)
+    lda_ok, lda_bad = 4227329, 4227330           # (127 lda + 16) * 8 < 2^32
+    ldb_ok, ldb_bad = 35791385, 35791386         # (15 ldb + 128) * 8 < 2^32
+    assert (127 * lda_ok + 16) * 8 < 2 ** 32 <= (127 * lda_bad + 16) * 8
+    assert (15 * ldb_ok + 128) * 8 < 2 ** 32 <= (15 * ldb_bad + 128) * 8
+    n = 256
+    for lda, ldb in ((lda_bad, n), (n, ldb_bad), (1 << 33, n)):
+        assert L.sw_leaf_gemm(n, 1, p(1), lda, 0, p(2), ldb, 0, p(3), n, 0, None) == sw.SW_EINVAL
+        assert "32-bit" in sw.sw_last_error()
+        assert L.sw_gemm_classical(n, n, n, p(1), lda, p(2), ldb, p(3), n, 0, None) == sw.SW_EINVAL
+        assert L.sw_gemm_ex(n, p(1), lda, p(2), ldb, p(3), n, 1, b"D", p(4), 1 << 30, None) == sw.SW_EINVAL
+        assert "32-bit" in sw.sw_last_error()
+        assert L.sw_gemm_rect(n, n, n, p(1), lda, p(2), ldb, p(3), n, 0, b"", None, 0, None) == sw.SW_EINVAL
+    sw.sw_set_workspace(None)
+    assert L.sw_dgemm(0, 0, n, n, n, 1.0, p(1), lda_bad, p(2), n, 0.0, p(3), n, 0, b"") == sw.SW_EINVAL
+    assert L.sw_dgemm(0, 0, n, n, n, 1.0, p(1), n, p(2), ldb_bad, 0.0, p(3), n, 0, b"") == sw.SW_EINVAL
+    # the record-only run takes the same path and accepts the largest pitches that fit
+    assert L.sw_trace_gemm(n, n, n, lda_ok, ldb_ok, n, 1, b"D", 1 << 30, 1, 0, -1, None, 0) > 0
+    assert L.sw_trace_gemm(n, n, n, lda_bad, ldb_ok, n, 1, b"D", 1 << 30, 1, 0, -1, None, 0) == sw.SW_EINVAL
