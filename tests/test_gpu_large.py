@@ -1,9 +1,14 @@
 """The three large configurations at full size, in the launch configuration the benchmark times.
 
-The CPU oracle cannot finish these in seconds, so they are checked on what it CAN compute one by one and on
-properties that hold at any size:
+The CPU oracle cannot finish these in seconds, so they are checked on what it CAN compute and on properties
+that hold at any size:
+  * configurations 3 and 4: about a hundred whole rows and a hundred whole columns of C, element by element,
+    against the oracle's strips of the definition; the rows and columns straddle every quadrant seam of every
+    level (the multiples of the leaf size, one below and at), the 128-wide tile edges inside several leaves,
+    the last partial tile of a leaf and the matrix border -- the places where an indexing mistake shows;
   * sampled entries C_ij against the oracle's definition-level dot product (long double accumulation) of
-    row i of A and column j of B, both regenerated on the host from the counter-based generator;
+    row i of A and column j of B, both regenerated on the host from the counter-based generator; the samples
+    are not random: they sit on the same seams, tile edges and partial tiles, in pairs that cross them;
   * Freivalds: C x against A (B x) for 8 random +-1 vectors, using torch's own GEMM (not this library);
   * integer-valued inputs, for which every intermediate is an exact integer: sampled entries and the
     Freivalds vectors must then agree EXACTLY.
@@ -28,16 +33,63 @@ def _free():
     torch.cuda.empty_cache()
 
 
-def _sample_indices(n, count, seed):
-    rng = np.random.default_rng(seed)
-    idx = rng.integers(0, n, size=(count, 2))
-    idx[0] = (0, 0)
-    idx[1] = (n - 1, n - 1)
-    idx[2] = (n // 2 - 1, n // 2)        # straddles the top-level quadrant seam
-    return idx
+def _marks(n, levels, want=None, seed=0):
+    """Row (or column) indices where mistakes show: one below and at every multiple of the leaf size (the quadrant
+    seams of all levels), the edges of the product kernel's 128-wide tiles and the last, partial tile inside the
+    first, a middle and the last leaf, and the border; filled up to `want` with seeded random ones."""
+    m = n >> levels
+    marks = {0, n - 1}
+    for b in range(m, n, m):
+        marks |= {b - 1, b}
+    last_tile = (m - 1) // 128 * 128                       # first row of the last tile of a leaf (partial unless 128 | m)
+    for leaf in (0, (n // m) // 2, n // m - 1):
+        base = leaf * m
+        for t in (1, 127, 128, 129, last_tile - 1, last_tile, last_tile + 1, m - 2):
+            if 0 <= t < m:
+                marks.add(base + t)
+    marks = sorted(marks)
+    if want is not None and len(marks) < want:
+        rng = np.random.default_rng(seed)
+        rest = np.setdiff1d(rng.integers(0, n, size=4 * want), marks)
+        marks = sorted(set(marks) | set(rest[: want - len(marks)].tolist()))
+    return np.array(marks, dtype=np.int64)
 
 
-def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=24):
+def _sample_indices(n, levels, count):
+    """Entries that cross the marks: every marked row with a marked column, walking both lists at coprime strides."""
+    marks = _marks(n, levels)
+    k = len(marks)
+    idx = [(0, 0), (n - 1, n - 1), (n // 2 - 1, n // 2), (n // 2, n // 2 - 1)]
+    import math
+    stride = next(q for q in (7, 5, 11, 13, 17) if math.gcd(q, k) == 1)
+    t = 0
+    while len(idx) < count:
+        idx.append((int(marks[t % k]), int(marks[(stride * t + 3) % k])))
+        t += 1
+    return np.array(idx[:count], dtype=np.int64)
+
+
+def _check_strips(oracle, C, A_host, B_host, levels, tol, exact, want):
+    """Whole rows and whole columns of the device result against the oracle's strips of the definition."""
+    from concurrent.futures import ThreadPoolExecutor
+    n = A_host.shape[0]
+    rows = _marks(n, levels, want, seed=1)
+    cols = _marks(n, levels, want, seed=2)
+    got_rows = C[torch.from_numpy(rows).to(C.device)].cpu().numpy()
+    got_cols = C[:, torch.from_numpy(cols).to(C.device)].cpu().numpy()
+    # the oracle is single-threaded; independent groups of rows / columns are handed to it from several threads
+    groups = lambda idx: [idx[k:k + 8] for k in range(0, len(idx), 8)]
+    with ThreadPoolExecutor(12) as pool:
+        ref_rows = np.concatenate(list(pool.map(lambda g: oracle.row_strip(A_host[g], B_host), groups(rows))), axis=0)
+        ref_cols = np.concatenate(list(pool.map(lambda g: oracle.col_strip(A_host, np.ascontiguousarray(B_host[:, g])), groups(cols))), axis=1)
+    if exact:
+        assert np.array_equal(got_rows, ref_rows) and np.array_equal(got_cols, ref_cols)
+    worst = max(float(np.max(np.abs(got_rows - ref_rows))), float(np.max(np.abs(got_cols - ref_cols))))
+    assert worst <= tol, (worst, tol)
+    return worst, len(rows), len(cols)
+
+
+def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=64, strips=0):
     n, levels, seed = cfg["n"], cfg["levels"], cfg["seed"]
     if host_pair is None:
         A = torch.empty((n, n), dtype=torch.float64, device=DEV)
@@ -65,7 +117,7 @@ def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=24):
     exact = dist == "integer"
 
     # sampled entries against the definition
-    idx = _sample_indices(n, samples, seed)
+    idx = _sample_indices(n, levels, samples)
     all_cols = np.arange(n)
     worst = 0.0
     for i, j in idx:
@@ -80,6 +132,21 @@ def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=24):
             assert got == ref, (i, j, got, ref)
         worst = max(worst, abs(got - ref))
     assert worst <= tol, (worst, tol)
+
+    # whole rows and columns, element by element
+    if strips:
+        if host_pair is None:
+            # the operands come from the seeded generator's device fill; tie the downloaded copies to the host generator
+            Ah, Bh = A.cpu().numpy(), B.cpu().numpy()
+            probe = np.array([0, n // 3, n - 1])
+            assert np.array_equal(Ah[probe], inputs.block(n, seed, 0, dist, probe, all_cols))
+            assert np.array_equal(Bh[:, probe], inputs.block(n, seed, 1, dist, all_cols, probe))
+        else:
+            Ah, Bh = host_pair
+        w, nr, nc = _check_strips(oracle, C, Ah, Bh, levels, tol, exact, strips)
+        print(f"{cfg['name']} {dist}: {nr} rows and {nc} columns element by element, max err {w:.3e} (tol {tol:.3e})")
+        worst = max(worst, w)
+        del Ah, Bh
 
     # Freivalds with 8 vectors of +-1 (their 1-norm is n)
     g = torch.Generator(device="cpu").manual_seed(seed)
@@ -101,25 +168,29 @@ def _check_product(oracle, cfg, dist, schedule, host_pair=None, samples=24):
 def test_configuration_3(oracle):
     cfg = inputs.CONFIGS[2]
     pair = inputs.pair(cfg)                      # standard normal: generated on the host and uploaded
-    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], cfg["schedule"], host_pair=pair)
-    print(f"cfg3 {s}: sampled max err {worst:.3e}, Freivalds {diff:.3e}")
+    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], cfg["schedule"], host_pair=pair, strips=128)
+    print(f"cfg3 {s}: max err {worst:.3e}, Freivalds {diff:.3e}")
 
 
 def test_configuration_3_integer(oracle):
     cfg = inputs.CONFIGS[2]
-    _check_product(oracle, cfg, "integer", cfg["schedule"])
+    _check_product(oracle, cfg, "integer", cfg["schedule"], strips=48)
 
 
 def test_configuration_4(oracle):
     cfg = inputs.CONFIGS[3]
-    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], cfg["schedule"])
-    print(f"cfg4 {s}: sampled max err {worst:.3e}, Freivalds {diff:.3e}")
-    _check_product(oracle, cfg, "integer", None)          # the planner's own order, exact arithmetic
+    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], cfg["schedule"], strips=112)
+    print(f"cfg4 {s}: max err {worst:.3e}, Freivalds {diff:.3e}")
+
+
+def test_configuration_4_integer_planner_order(oracle):
+    cfg = inputs.CONFIGS[3]
+    _check_product(oracle, cfg, "integer", None, strips=80)          # the planner's own order, exact arithmetic
 
 
 def test_configuration_5(oracle):
     cfg = inputs.CONFIGS[4]
-    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], None)
+    s, worst, diff = _check_product(oracle, cfg, cfg["dist"], None, samples=96)
     print(f"cfg5 {s}: sampled max err {worst:.3e}, Freivalds {diff:.3e}")
     assert s == "DDDBB"
 
