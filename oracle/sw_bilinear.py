@@ -7,7 +7,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsw_bilinear_oracle.so")
 _lib = None
-STRASSEN, CLASSICAL8 = 0, 1
+STRASSEN, CLASSICAL8, LADERMAN, CLASSICAL27 = 0, 1, 2, 3
 
 
 class Counters(ctypes.Structure):
@@ -27,7 +27,9 @@ def lib():
         dp = ctypes.POINTER(ctypes.c_double)
         L.sw_bilinear_gemm.argtypes = [ctypes.c_int64, dp, dp, dp, ctypes.c_int, ctypes.c_int]
         L.sw_bilinear_gemm.restype = ctypes.c_int
-        L.sw_bilinear_tables.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.sw_bilinear_gemm_levels.argtypes = [ctypes.c_int64, dp, dp, dp, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.sw_bilinear_gemm_levels.restype = ctypes.c_int
+        L.sw_bilinear_tables.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.sw_bilinear_tables.restype = ctypes.c_int
         L.sw_bilinear_get_counters.argtypes = [ctypes.POINTER(Counters)]
         _lib = L
@@ -35,23 +37,32 @@ def lib():
 
 
 def gemm(A, B, levels, scheme):
+    """C = A @ B by `levels` steps of one scheme (an int) or of one scheme per level (a sequence, top level first)."""
     A = np.ascontiguousarray(A, dtype=np.float64)
     B = np.ascontiguousarray(B, dtype=np.float64)
     n = A.shape[0]
     C = np.empty_like(A)
     p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
-    rc = lib().sw_bilinear_gemm(n, p(A), p(B), p(C), int(levels), int(scheme))
+    per_level = [int(scheme)] * int(levels) if np.isscalar(scheme) else [int(x) for x in scheme]
+    if len(per_level) != int(levels):
+        raise ValueError("one scheme per level")
+    arr = (ctypes.c_int * max(1, len(per_level)))(*per_level)
+    rc = lib().sw_bilinear_gemm_levels(n, p(A), p(B), p(C), int(levels), arr)
     if rc != 0:
-        raise RuntimeError(f"sw_bilinear_gemm failed with {rc}")
+        raise RuntimeError(f"sw_bilinear_gemm_levels failed with {rc}")
     return C
 
 
 def tables(scheme):
-    """(U, V, W) as integer arrays of shapes (q, 4), (q, 4), (4, q)."""
-    buf = (ctypes.c_int * 96)()
-    q = lib().sw_bilinear_tables(int(scheme), buf)
-    v = np.array(buf[: 12 * q], dtype=np.int64)
-    return v[: 4 * q].reshape(q, 4), v[4 * q: 8 * q].reshape(q, 4), v[8 * q:].reshape(4, q)
+    """(U, V, W, n0) with integer arrays of shapes (q, n0^2), (q, n0^2), (n0^2, q)."""
+    buf = (ctypes.c_int * (3 * 27 * 9))()
+    n0 = ctypes.c_int(0)
+    q = lib().sw_bilinear_tables(int(scheme), buf, ctypes.byref(n0))
+    if q < 0:
+        raise ValueError("unknown scheme")
+    b = n0.value ** 2
+    v = np.array(buf[: 3 * q * b], dtype=np.int64)
+    return v[: q * b].reshape(q, b), v[q * b: 2 * q * b].reshape(q, b), v[2 * q * b:].reshape(b, q), n0.value
 
 
 def reset_counters():
