@@ -53,6 +53,21 @@ int sw_gemm(int64_t n, const double* A, const double* B, double* C, int levels, 
 int sw_gemm_ex(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
                int levels, const char* schedule, void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): sw_gemm_ex with the workspace taken from an array of SW_STATIC_SCRATCH_BYTES that is part
+ * of the library's device image (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates nothing: no hipMalloc or hipFree, no streams, no events.  Everything runs on `hip_stream` (the
+ * one-stream executor); sw_set_overlap, sw_set_odd_mode and sw_profile_enable do not apply (odd n is zero-padded
+ * inside the scratch).  schedule NULL or "": the planner's choice for SW_STATIC_SCRATCH_BYTES; levels < 0: the
+ * depth by the cost model for that size.  Same arguments, results (bit for bit) and errors as sw_gemm_ex;
+ * SW_ENOMEM, before anything is enqueued, when the product at this depth and step order needs more than the
+ * scratch holds (the all-DFS order of sw_plan_memory is the least: n = 4096 at three levels takes 90 MB).
+ * All calls on one GPU share that GPU's array: nothing in it needs clearing between calls (every buffer is
+ * written before it is read), but two calls that overlap in time on one GPU race, whatever their streams. */
+#define SW_STATIC_SCRATCH_BYTES (128 * 1024 * 1024)
+int sw_gemm_static(int64_t n, const double* A, int64_t lda, const double* B, int64_t ldb, double* C, int64_t ldc,
+                   int levels, const char* schedule, void* hip_stream);
+
 /* The same recursion on a rectangular product: C (M x N) = A (M x K) * B (K x N), row-major with leading
  * dimensions lda >= K, ldb >= N, ldc >= N.  Every step halves all three extents: the operands T are
  * M/2 x K/2, S are K/2 x N/2, the products Q are M/2 x N/2 (Appendix A holds for any conformal 2 x 2

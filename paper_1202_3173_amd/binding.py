@@ -17,7 +17,7 @@ EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
            "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
-           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm")
+           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm", "sw_gemm_static")
 
 
 class SwError(RuntimeError):
@@ -47,6 +47,7 @@ def lib():
     sig = {
         "sw_gemm": (ci, [i64, vp, vp, vp, ci, cp]),
         "sw_gemm_ex": (ci, [i64, vp, i64, vp, i64, vp, i64, ci, cp, vp, i64, vp]),
+        "sw_gemm_static": (ci, [i64, vp, i64, vp, i64, vp, i64, ci, cp, vp]),
         "sw_plan_memory": (i64, [i64, ci, cp]),
         "sw_gemm_scaled": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_scaled": (i64, [i64, ci, cp]),
@@ -272,6 +273,17 @@ def sw_gemm_ex(n, A, lda, B, ldb, C, ldc, levels, schedule, workspace, stream_ha
     st = _stream(C) if stream_handle is None else ctypes.c_void_p(stream_handle)
     return _check(lib().sw_gemm_ex(n, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, levels, _sched(schedule),
                                    ws_ptr, ws_bytes, st))
+
+
+SW_STATIC_SCRATCH_BYTES = 128 * 1024 * 1024
+
+
+def sw_gemm_static(n, A, lda, B, ldb, C, ldc, levels, schedule, stream_handle=None):
+    """sw_gemm_ex on the library's own static scratch: allocates nothing (the caller passes C)."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+    st = _stream(C) if stream_handle is None else ctypes.c_void_p(stream_handle)
+    return _check(lib().sw_gemm_static(n, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, levels, _sched(schedule), st))
 
 
 def sw_pre_add(side, parent, parent_ld, parent_stride, live, h, child, child_ld, child_stride):

@@ -266,9 +266,23 @@ def test_leading_dimensions_beyond_the_product_kernels_reach_are_refused():
         assert L.sw_gemm_ex(n, p(1), lda, p(2), ldb, p(3), n, 1, b"D", p(4), 1 << 30, None) == sw.SW_EINVAL
         assert "32-bit" in sw.sw_last_error()
         assert L.sw_gemm_rect(n, n, n, p(1), lda, p(2), ldb, p(3), n, 0, b"", None, 0, None) == sw.SW_EINVAL
+        assert L.sw_gemm_static(n, p(1), lda, p(2), ldb, p(3), n, 1, b"D", None) == sw.SW_EINVAL
     sw.sw_set_workspace(None)
     assert L.sw_dgemm(0, 0, n, n, n, 1.0, p(1), lda_bad, p(2), n, 0.0, p(3), n, 0, b"") == sw.SW_EINVAL
     assert L.sw_dgemm(0, 0, n, n, n, 1.0, p(1), n, p(2), ldb_bad, 0.0, p(3), n, 0, b"") == sw.SW_EINVAL
     # the record-only run takes the same path and accepts the largest pitches that fit
     assert L.sw_trace_gemm(n, n, n, lda_ok, ldb_ok, n, 1, b"D", 1 << 30, 1, 0, -1, None, 0) > 0
     assert L.sw_trace_gemm(n, n, n, lda_bad, ldb_ok, n, 1, b"D", 1 << 30, 1, 0, -1, None, 0) == sw.SW_EINVAL
+
+
+def test_static_scratch_limit_is_checked_on_the_host():
+    """sw_gemm_static refuses, before it touches the device, a product whose workspace exceeds its array."""
+    import ctypes
+    L = sw.lib()
+    p = lambda k: ctypes.c_void_p(k << 40)
+    assert sw.sw_plan_memory(8192, 2, "DD") > sw.SW_STATIC_SCRATCH_BYTES
+    assert L.sw_gemm_static(8192, p(1), 8192, p(2), 8192, p(3), 8192, 2, b"DD", None) == sw.SW_ENOMEM
+    assert "static scratch" in sw.sw_last_error()
+    header = open(os.path.join(ROOT, "include", "sw_gemm.h")).read()
+    assert re.search(r"#define SW_STATIC_SCRATCH_BYTES \(128 \* 1024 \* 1024\)", header)
+    assert sw.SW_STATIC_SCRATCH_BYTES == 128 * 1024 * 1024
