@@ -93,25 +93,38 @@ int64_t sw_plan_memory_scaled(int64_t n, int levels, const char* schedule);
 
 /* ---- other recursive algorithms on the same BFS/DFS machinery (Section 6.6) ------------------------------- */
 
-/* C = A*B by a recursion built on another 2 x 2 block scheme with q products: q combinations of the quadrants
- * of A and of B are multiplied pairwise (recursively) and combined into the quadrants of C.  A BFS step keeps
- * T, S, Q of all q subproblems of every parent (3q half-size buffers), a DFS step solves them in sequence (3
- * buffers).  scheme: SW_SCHEME_WINOGRAD = sw_gemm itself; SW_SCHEME_STRASSEN = Strassen's original algorithm
- * (7 products, 18 additions per step, the count behind the constants of Section 3.3.2); SW_SCHEME_CLASSICAL =
- * the classical algorithm written recursively (8 products, 4 additions; Section 6.6.1), whose rounding errors
- * obey the classical component-wise bound.  Every combination is summed left to right over the quadrants 11,
- * 12, 21, 22 (over the products in their order), so all step orders give the same bits.  Same arguments,
- * state (workspace, stream), padding rule and errors as sw_gemm; the workspace must hold
- * sw_plan_memory_bilinear bytes; additionally SW_EINVAL for an unknown scheme or when q^(BFS steps) leaf
- * products do not fit one launch.  Runs on one stream. */
+/* C = A*B by a recursion built on another block scheme: a way to multiply n0 x n0 block matrices with q block
+ * products (Section 6.6.2: exponent w0 = log_n0 q).  q combinations of the blocks of A and of B are multiplied
+ * pairwise (recursively) and combined into the blocks of C.  A BFS step keeps T, S, Q of all q subproblems of
+ * every parent (3q buffers of 1/n0 the size), a DFS step solves them in sequence (3 buffers).
+ * scheme: SW_SCHEME_WINOGRAD = sw_gemm itself; SW_SCHEME_STRASSEN = Strassen's original algorithm (2 x 2 blocks,
+ * 7 products, 18 additions per step, the count behind the constants of Section 3.3.2); SW_SCHEME_CLASSICAL = the
+ * classical algorithm written recursively on 2 x 2 blocks (8 products, 4 additions; Section 6.6.1), whose
+ * rounding errors obey the classical component-wise bound; SW_SCHEME_LADERMAN = Laderman's algorithm on 3 x 3
+ * blocks (23 products); SW_SCHEME_CLASSICAL3 = the classical algorithm on 3 x 3 blocks (27 products).  Every
+ * combination is summed left to right over the blocks 11, 12, .. (over the products in their order), so all
+ * step orders give the same bits.  Same arguments, state (workspace, stream) and errors as sw_gemm; n that the
+ * levels' block counts do not divide is zero-padded to the next multiple of their product; the workspace must
+ * hold sw_plan_memory_bilinear bytes; additionally SW_EINVAL for an unknown scheme, when the levels cut n into
+ * more parts than it has rows, or when the leaf products of one launch (q per BFS step) do not fit one
+ * launch.  Runs on one stream. */
 #define SW_SCHEME_WINOGRAD 0
 #define SW_SCHEME_STRASSEN 1
 #define SW_SCHEME_CLASSICAL 2
+#define SW_SCHEME_LADERMAN 3
+#define SW_SCHEME_CLASSICAL3 4
 int sw_gemm_bilinear(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule,
                      int scheme);
-/* Workspace bytes of sw_gemm_bilinear (schedule NULL or "": all-DFS, the minimum).  Host arithmetic only. */
+/* The same with one scheme per level: schemes is a HOST array of `levels` scheme numbers, top level first (any but
+ * SW_SCHEME_WINOGRAD), so steps on 2 x 2 and on 3 x 3 blocks mix: n = 94080 = 2^7 * 3 * 5 * 7^2 takes four Strassen
+ * steps and one Laderman step without padding. */
+int sw_gemm_bilinear_levels(int64_t n, const double* A, const double* B, double* C, int levels, const char* schedule,
+                            const int* schemes);
+/* Workspace bytes of sw_gemm_bilinear / sw_gemm_bilinear_levels (schedule NULL or "": all-DFS, the minimum).
+ * Host arithmetic only. */
 int64_t sw_plan_memory_bilinear(int64_t n, int levels, const char* schedule, int scheme);
-/* Floating-point operations of the scheme's recursion, n a multiple of 2^levels (classical leaves 2m^3 - m^2,
+int64_t sw_plan_memory_bilinear_levels(int64_t n, int levels, const char* schedule, const int* schemes);
+/* Floating-point operations of the scheme's recursion, n a multiple of n0^levels (classical leaves 2m^3 - m^2,
  * one operation per element and block addition); -1.0 for bad arguments.  Host arithmetic only. */
 double sw_flop_count_bilinear(int64_t n, int levels, int scheme);
 

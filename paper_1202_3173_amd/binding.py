@@ -17,7 +17,7 @@ EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
            "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
-           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm", "sw_gemm_static")
+           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm", "sw_gemm_static", "sw_gemm_bilinear_levels", "sw_plan_memory_bilinear_levels")
 
 
 class SwError(RuntimeError):
@@ -61,6 +61,8 @@ def lib():
         "sw_gemm_bilinear": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_bilinear": (i64, [i64, ci, cp, ci]),
         "sw_flop_count_bilinear": (dbl, [i64, ci, ci]),
+        "sw_gemm_bilinear_levels": (ci, [i64, vp, vp, vp, ci, cp, ctypes.POINTER(ci)]),
+        "sw_plan_memory_bilinear_levels": (i64, [i64, ci, cp, ctypes.POINTER(ci)]),
         "sw_plan_workspace": (i64, [i64, ci, cp, i64]),
         "sw_plan_schedule": (ci, [i64, ci, i64, ctypes.c_char_p]),
         "sw_model_words": (i64, [i64, ci, cp]),
@@ -245,7 +247,26 @@ def sw_model_seconds(n, levels, budget_bytes):
     return lib().sw_model_seconds(n, levels, int(budget_bytes))
 
 
-SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL = 0, 1, 2
+SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL, SW_SCHEME_LADERMAN, SW_SCHEME_CLASSICAL3 = 0, 1, 2, 3, 4
+SCHEME_BASE = {SW_SCHEME_WINOGRAD: 2, SW_SCHEME_STRASSEN: 2, SW_SCHEME_CLASSICAL: 2, SW_SCHEME_LADERMAN: 3, SW_SCHEME_CLASSICAL3: 3}
+SCHEME_PRODUCTS = {SW_SCHEME_WINOGRAD: 7, SW_SCHEME_STRASSEN: 7, SW_SCHEME_CLASSICAL: 8, SW_SCHEME_LADERMAN: 23, SW_SCHEME_CLASSICAL3: 27}
+
+
+def _schemes(schemes):
+    return (ctypes.c_int * max(1, len(schemes)))(*[int(x) for x in schemes])
+
+
+def sw_gemm_bilinear_levels(n, A, B, C, schedule, schemes):
+    """C = A @ B with one block scheme per level (top level first) through the library state."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C")):
+        _f64_cuda(t, name)
+        if not t.is_contiguous() or tuple(t.shape) != (n, n):
+            raise ValueError(f"{name} must be a contiguous {n} x {n} tensor")
+    return _check(lib().sw_gemm_bilinear_levels(n, _ptr(A), _ptr(B), _ptr(C), len(schemes), _sched(schedule), _schemes(schemes)))
+
+
+def sw_plan_memory_bilinear_levels(n, schedule, schemes):
+    return _check(lib().sw_plan_memory_bilinear_levels(n, len(schemes), _sched(schedule), _schemes(schemes)))
 
 
 def sw_gemm_bilinear(n, A, B, C, levels, schedule, scheme):

@@ -192,6 +192,29 @@ def test_bilinear_memory_and_flop_counts(oracle):
         sw_bilinear.gemm(A, A, 2, oid)
         c = sw_bilinear.counters()
         assert sw.sw_flop_count_bilinear(m, 2, scheme) == c["leaf_mul"] + c["leaf_add"] + c["block_add"]
+    # 3 x 3 blocks: the step divides by three, q = 23 or 27 children; levels may carry different schemes
+    for scheme, q, oid in ((sw.SW_SCHEME_LADERMAN, 23, 2), (sw.SW_SCHEME_CLASSICAL3, 27, 3)):
+        n, levels = 1458, 3
+        want, live, size = 0, 1, n
+        for ch in "BDB":
+            size //= 3
+            want += (3 * q if ch == "B" else 3) * live * ws_mat_elems(size) * 8
+            live *= q if ch == "B" else 1
+        assert sw.sw_plan_memory_bilinear(n, levels, "BDB", scheme) == want
+        assert sw.sw_plan_memory_bilinear(1000, 2, "DD", scheme) == sw.sw_plan_memory_bilinear(1008, 2, "DD", scheme) + 3 * ws_mat_elems(1008) * 8
+        m = 54
+        A = inputs.matrix(m, 1, 0, "integer")
+        sw_bilinear.reset_counters()
+        sw_bilinear.gemm(A, A, 2, oid)
+        c = sw_bilinear.counters()
+        assert sw.sw_flop_count_bilinear(m, 2, scheme) == c["leaf_mul"] + c["leaf_add"] + c["block_add"]
+        assert sw.sw_flop_count_bilinear(m + 1, 2, scheme) == -1.0
+    mixed = [sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_LADERMAN]
+    assert sw.sw_plan_memory_bilinear_levels(600, "BD", mixed) == (21 * ws_mat_elems(300) + 3 * 7 * ws_mat_elems(100)) * 8
+    assert sw.sw_plan_memory_bilinear_levels(600, "DB", mixed) == (3 * ws_mat_elems(300) + 3 * 23 * ws_mat_elems(100)) * 8
+    assert sw.sw_plan_memory_bilinear_levels(601, "DB", mixed) == sw.sw_plan_memory_bilinear_levels(606, "DB", mixed) + 3 * ws_mat_elems(606) * 8
+    with pytest.raises(sw.SwError):
+        sw.sw_plan_memory_bilinear_levels(600, "DB", [sw.SW_SCHEME_STRASSEN, sw.SW_SCHEME_WINOGRAD])
     assert sw.sw_flop_count_bilinear(4096, 3, sw.SW_SCHEME_CLASSICAL) == 2.0 * 4096 ** 3 - 4096 ** 2
     assert sw.sw_flop_count_bilinear(4096, 3, sw.SW_SCHEME_WINOGRAD) == sw.sw_flop_count(4096, 3)
     assert sw.sw_plan_memory_bilinear(4096, 3, "BBB", sw.SW_SCHEME_WINOGRAD) == sw.sw_plan_memory(4096, 3, "BBB")
