@@ -81,8 +81,13 @@ def main():
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
     ap.add_argument("--overlap", type=int, default=None, help="0: one stream; 1 (default): three streams, leaf-side addition kernels sized to their work; k > 1: capped at k workgroups")
-    ap.add_argument("--scheme", choices=["winograd", "strassen", "classical"], default="winograd",
-                    help="the 2 x 2 block scheme under the recursion (Section 6.6); default: the Strassen-Winograd path")
+    ap.add_argument("--scheme", default="winograd",
+                    help="the block scheme under the recursion (Section 6.6): winograd (default, the Strassen-Winograd path), strassen, "
+                         "classical, laderman, classical3, or one per level separated by commas (top level first), e.g. "
+                         "strassen,strassen,strassen,strassen,laderman")
+    ap.add_argument("--budget-gb", type=float, default=None,
+                    help="total device memory the product may use, in GB of 10^9 bytes, A, B and C included "
+                         "(default: what is free on the device)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reference", action="store_true", help="skip the extra single-stream product after the timed steps")
     args = ap.parse_args()
@@ -110,7 +115,25 @@ def main():
     C = torch.empty((n, n), dtype=torch.float64, device=dev)
     free, total_mem = torch.cuda.mem_get_info()
     budget = int(free - (2 << 30))
-    scheme = {"winograd": sw.SW_SCHEME_WINOGRAD, "strassen": sw.SW_SCHEME_STRASSEN, "classical": sw.SW_SCHEME_CLASSICAL}[args.scheme]
+    if args.budget_gb is not None:
+        budget = min(budget, int(args.budget_gb * 1e9) - 3 * n * n * 8)
+        if budget < 0:
+            sys.exit(f"bench.py: A, B and C alone take {3 * n * n * 8 / 1e9:.1f} GB")
+    ids = {"winograd": sw.SW_SCHEME_WINOGRAD, "strassen": sw.SW_SCHEME_STRASSEN, "classical": sw.SW_SCHEME_CLASSICAL,
+           "laderman": sw.SW_SCHEME_LADERMAN, "classical3": sw.SW_SCHEME_CLASSICAL3}
+    names = args.scheme.split(",")
+    if any(x not in ids for x in names) or (len(names) > 1 and "winograd" in names):
+        sys.exit("bench.py: --scheme takes winograd, or strassen / classical / laderman / classical3 (one, or one per level)")
+    per_level = [ids[x] for x in names] if len(names) > 1 else None
+    scheme = ids[names[0]]
+    if per_level is not None:
+        levels = len(per_level)
+        cfg.update(levels=levels, schedule=None)
+    elif scheme != sw.SW_SCHEME_WINOGRAD:
+        per_level = [scheme] * levels
+    radix = 1
+    for x in (per_level or [sw.SW_SCHEME_WINOGRAD] * levels):
+        radix *= sw.SCHEME_BASE[x]
     if scheme == sw.SW_SCHEME_WINOGRAD:
         schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, budget)
         if levels == 0:
@@ -119,12 +142,13 @@ def main():
     else:
         # the comparison schemes: most BFS steps that fit, then least memory (the library's own preference)
         orders = ["".join("B" if (mask >> i) & 1 else "D" for i in range(levels)) for mask in range(1 << levels)]
-        fits = [(-o.count("B"), sw.sw_plan_memory_bilinear(n, levels, o, scheme), o) for o in orders]
-        fits = [f for f in fits if f[1] <= budget and 8 ** -f[0] <= 4096]
+        batch_of = lambda o: int(__import__("math").prod(sw.SCHEME_PRODUCTS[x] for x, ch in zip(per_level, o) if ch == "B"))
+        fits = [(-o.count("B"), sw.sw_plan_memory_bilinear_levels(n, o, per_level), o) for o in orders]
+        fits = [f for f in fits if f[1] <= budget and batch_of(f[2]) <= 4096]
         if args.schedule is None and not fits:
             sys.exit("bench.py: no step order of this scheme fits the free device memory")
         schedule = args.schedule if args.schedule is not None else min(fits)[2]
-        need = sw.sw_plan_memory_bilinear(n, levels, schedule, scheme)
+        need = sw.sw_plan_memory_bilinear_levels(n, schedule, per_level)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     if scheme != sw.SW_SCHEME_WINOGRAD:
@@ -135,7 +159,7 @@ def main():
         if scheme == sw.SW_SCHEME_WINOGRAD:
             sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, schedule, ws, stream)
         else:
-            sw.sw_gemm_bilinear(n, A, B, C, levels, schedule, scheme)
+            sw.sw_gemm_bilinear_levels(n, A, B, C, schedule, per_level)
 
     for _ in range(args.warmup):
         step()
@@ -177,12 +201,16 @@ def main():
     eff_gflops = 2.0 * n ** 3 / (dt / args.steps) / 1e9
 
     leaf = prof["leaf_gemm"]
-    leaf_batch = (8 if args.scheme == "classical" else 7) ** schedule.count("B")   # leaves per launch
+    leaf_batch = 1                                                                  # leaves per launch
+    for x, ch in zip(per_level or [sw.SW_SCHEME_WINOGRAD] * levels, schedule):
+        leaf_batch *= sw.SCHEME_PRODUCTS[x] if ch == "B" else 1
     leaf_tflops = leaf["work"] / (leaf["ms"] * 1e-3) / 1e12 if leaf["ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": "leaf_gemm_kernel (batched fp64 MFMA)",
                 "achieved": round(leaf_tflops, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(leaf_tflops / FP64_MFMA_PEAK_TFLOPS, 4),
-                "traffic": measured_traffic(n >> levels, leaf_batch),
+                "traffic": measured_traffic(n // radix, leaf_batch),
+                "traffic_source": "the committed rocprofv3 counter summary of this launch shape under profiles/ (FETCH_SIZE and WRITE_SIZE "
+                                  "runs scaled by a copy of known size); a constant, not measured in this run; null when no summary covers the shape",
                 "launches": leaf["launches"], "avg_launch_ms": round(leaf["ms"] / max(1, leaf["launches"]), 4),
                 "flops_per_launch": leaf["work"] / max(1, leaf["launches"]),
                 "note": ("timed with the default executor: addition kernels run beside the leaf launches on other streams and "
@@ -208,21 +236,27 @@ def main():
     absmax = lambda t: max(float(t[r:r + 4096].abs().max()) for r in range(0, n, 4096))   # chunked: no n x n temporary
     tol = 1e-10 * n * absmax(A) * absmax(B)
 
+    # the algorithm's own operation count (closed form; one scheme for all levels, n divisible by the levels' radices)
+    flops_actual = sw.sw_flop_count_bilinear(n, levels, scheme) if (n % radix == 0 and len(names) == 1) else None
+
     out = {
         "metric": "effective fp64 GFLOP/s (2n^3/t)", "value": round(eff_gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: n={n} square fp64 C=A*B, {levels} "
-                               + {"winograd": "Strassen-Winograd", "strassen": "Strassen (original)", "classical": "recursive classical"}[args.scheme] + " levels, "
-                               f"leaf {n >> levels}, entries {cfg['dist']} seed {cfg['seed']}"
-                               + (f", odd size handled by {args.odd_mode}" if n % (1 << levels) else ""),
+                               + ({"winograd": "Strassen-Winograd", "strassen": "Strassen (original)", "classical": "recursive classical",
+                                   "laderman": "Laderman (3 x 3 blocks)", "classical3": "recursive classical (3 x 3 blocks)"}[names[0]]
+                                  if len(names) == 1 else "mixed (" + args.scheme + ")") + " levels, "
+                               f"leaf {-(-n // radix)}, entries {cfg['dist']} seed {cfg['seed']}"
+                               + (f", odd size handled by {args.odd_mode if scheme == sw.SW_SCHEME_WINOGRAD else 'pad'}" if n % radix else ""),
                    "n": n, "levels": levels, "schedule": schedule, "workspace_GB": round(need / 1e9, 3),
-                   "hbm_total_GB": round(total_mem / 1e9, 1)},
+                   "hbm_total_GB": round(total_mem / 1e9, 1),
+                   "memory_budget_GB": args.budget_gb, "operands_plus_workspace_GB": round((3 * n * n * 8 + need) / 1e9, 3)},
         "pct_of_fp64_mfma_peak": round(100.0 * eff_gflops / (FP64_MFMA_PEAK_TFLOPS * 1e3), 2),
-        "actual_flops_per_step": sw.sw_flop_count_bilinear(n, levels, scheme) if n % (1 << levels) == 0 else None,
+        "actual_flops_per_step": flops_actual,
         # Section 6.3's yardstick: the time the algorithm's own flop count would take at the machine's peak
-        "pct_of_algorithm_peak": (round(100.0 * sw.sw_flop_count_bilinear(n, levels, scheme) / (dt / args.steps) / (FP64_MFMA_PEAK_TFLOPS * 1e12), 2)
-                                  if n % (1 << levels) == 0 else None),
+        "pct_of_algorithm_peak": (round(100.0 * flops_actual / (dt / args.steps) / (FP64_MFMA_PEAK_TFLOPS * 1e12), 2)
+                                  if flops_actual else None),
         "roofline": roofline,
         "additions": {"GBps_all": round(add_gbps, 1), "frac_of_hbm_peak": round(add_gbps / HBM_PEAK_GBPS, 4),
                       "ms_per_step": round(add_ms / args.steps, 3), "by_class": adds,

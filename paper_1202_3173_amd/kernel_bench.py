@@ -8,6 +8,14 @@
                                                                             # the general product (alpha, beta,
                                                                             # transposes, rectangular), 2MNK/t
 
+  python -m paper_1202_3173_amd.kernel_bench depth --sizes 4096,8192 --max-levels 6
+                                                                            # whole product against the depth,
+                                                                            # next to what sw_plan_levels picks
+  python -m paper_1202_3173_amd.kernel_bench orders --n 16384 --levels 4     # whole product for every step order
+                                                                            # that fits, next to the planner's pick
+  python -m paper_1202_3173_amd.kernel_bench error_growth --n 2048           # error against the depth, with and
+                                                                            # without diagonal scaling (Section 6.1)
+
 Each kernel is launched `--iters` times between two HIP events on the launch stream; one JSON line reports
 the average duration and the achieved rate on ALGORITHMIC work: 2 m^3 flops per leaf product; for the
 additions the distinct elements read plus written, times 8 bytes (pre-add: 4 quadrants in, 7 operands out;
@@ -37,9 +45,139 @@ def _timed(fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
+def _best_of(fn, reps=3):
+    """Wall time of the best of `reps` runs after one warm-up (whole products: host-side clock around a sync)."""
+    import time
+    import torch
+    best = float("inf")
+    for rep in range(reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        if rep:
+            best = min(best, time.perf_counter() - t0)
+    return best
+
+
+def depth_study(sizes, max_levels):
+    """For every n and every depth the planner's step order for the free device memory is timed on seeded uniform
+    inputs generated in HBM; one line per (n, depth) and one per n with the measured optimum and the model's choice."""
+    import torch
+    from . import binding as sw
+    from . import inputs
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    for n in sizes:
+        A, B = inputs.device_pair({"n": n, "seed": 11, "dist": "uniform"}, dev)
+        C = torch.empty((n, n), dtype=torch.float64, device=dev)
+        free, _ = torch.cuda.mem_get_info()
+        budget = int(free - (2 << 30))
+        rows = []
+        for L in range(0, max_levels + 1):
+            if (n >> L) < 64:
+                break
+            try:
+                order = sw.sw_plan_schedule(n, L, budget) if L else ""
+            except sw.SwError:
+                continue
+            ws = torch.empty(max(sw.sw_plan_workspace(n, L, order, budget), 256), dtype=torch.uint8, device=dev)
+            best = _best_of(lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, L, order, ws, stream))
+            del ws
+            rows.append((L, order, best))
+            print(f"n {n} levels {L} order {order or '-'} ms {best * 1e3:.3f} effective_TFLOPs {2.0 * n ** 3 / best / 1e12:.2f}", flush=True)
+        measured = min(rows, key=lambda r: r[2])
+        picked = sw.sw_plan_levels(n, budget)
+        t_picked = next(r[2] for r in rows if r[0] == picked)
+        print(f"n {n}: measured optimum {measured[0]} levels ({measured[2] * 1e3:.3f} ms), sw_plan_levels picks {picked} "
+              f"({t_picked * 1e3:.3f} ms, {100.0 * (t_picked / measured[2] - 1):.1f} % above the optimum)", flush=True)
+        del A, B, C
+        torch.cuda.empty_cache()
+
+
+def order_study(n, levels, dist, seed):
+    """Every step order of `levels` steps that fits the free device memory, timed on the whole product, next to the
+    planner's pick (sw_plan_schedule) for the same budget."""
+    import torch
+    from . import binding as sw
+    from . import inputs
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    A, B = inputs.device_pair({"n": n, "seed": seed, "dist": dist}, dev)
+    C = torch.empty((n, n), dtype=torch.float64, device=dev)
+    free, _ = torch.cuda.mem_get_info()
+    budget = int(free - (2 << 30))
+    picked = sw.sw_plan_schedule(n, levels, budget)
+    rows = []
+    for mask in range(1 << levels):
+        order = "".join("B" if (mask >> i) & 1 else "D" for i in range(levels))
+        if sw.sw_plan_memory(n, levels, order) > budget:
+            continue
+        ws = torch.empty(max(sw.sw_plan_workspace(n, levels, order, budget), 256), dtype=torch.uint8, device=dev)
+        t = _best_of(lambda: sw.sw_gemm_ex(n, A, n, B, n, C, n, levels, order, ws, stream))
+        del ws
+        torch.cuda.empty_cache()
+        rows.append((order, t))
+        print(f"n {n} order {order} ms {t * 1e3:.3f} effective_TFLOPs {2.0 * n ** 3 / t / 1e12:.2f}" + ("   <- planner" if order == picked else ""), flush=True)
+    best = min(rows, key=lambda r: r[1])
+    t_picked = next(t for o, t in rows if o == picked)
+    print(f"n {n} levels {levels}: best order {best[0]} ({best[1] * 1e3:.3f} ms), planner picks {picked} ({t_picked * 1e3:.3f} ms, "
+          f"{100.0 * (t_picked / best[1] - 1):.1f} % above the best)", flush=True)
+
+
+def error_growth(n):
+    """Markdown tables: the largest entry-wise error relative to ||A(i,:)|| ||B(:,j)|| (the quantity the scaled bound
+    of Section 6.1 is stated in) in units of n*eps, and in brackets the norm-wise error in units of
+    n*eps*||A||*||B|| (max-norms), against a product accumulated in extended precision on the host."""
+    import numpy as np
+    import torch
+    from . import binding as sw
+    from . import inputs
+    dev = "cuda:0"
+
+    def run(A, B, levels, mode):
+        dA, dB = torch.from_numpy(A).to(dev), torch.from_numpy(B).to(dev)
+        C = torch.empty((n, n), dtype=torch.float64, device=dev)
+        schedule = "B" * levels
+        ws = torch.empty(sw.sw_plan_memory_scaled(n, levels, schedule), dtype=torch.uint8, device=dev)
+        sw.sw_set_workspace(ws)
+        sw.sw_set_stream(torch.cuda.current_stream().cuda_stream)
+        try:
+            sw.sw_gemm_scaled(n, dA, dB, C, levels, schedule, mode)
+            torch.cuda.synchronize()
+        finally:
+            sw.sw_set_workspace(None)
+            sw.sw_set_stream(0)
+        return C.cpu().numpy()
+
+    eps = np.finfo(float).eps
+    for dist in ("badscaled", "rowscaled", "uniform"):
+        A = inputs.matrix(n, 77, 0, dist)
+        B = inputs.matrix(n, 77, 1, dist)
+        ref = (A.astype(np.longdouble) @ B.astype(np.longdouble)).astype(np.float64)
+        rowcol = np.max(np.abs(A), axis=1)[:, None] * np.max(np.abs(B), axis=0)[None, :]
+        norm = np.max(np.abs(A)) * np.max(np.abs(B))
+        print(f"\n### {dist}, n = {n}\n")
+        print("| levels | plain | outside (D1, D3) | inside (D2) | both |")
+        print("|---|---|---|---|---|")
+        for levels in range(0, 6):
+            cells = []
+            for mode in (0, sw.SW_SCALE_OUTSIDE, sw.SW_SCALE_INSIDE, sw.SW_SCALE_OUTSIDE | sw.SW_SCALE_INSIDE):
+                C = run(A, B, levels, mode)
+                cells.append(f"{np.max(np.abs(C - ref) / rowcol) / (n * eps):.3g} [{np.max(np.abs(C - ref)) / (n * eps * norm):.2g}]")
+            print(f"| {levels} | " + " | ".join(cells) + " |")
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "copy", "dgemm"])
+    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "copy", "dgemm", "depth", "orders", "error_growth"])
+    ap.add_argument("--sizes", default="2048,4096,8192,16384,23520,32768,47040", help="depth: the sizes n")
+    ap.add_argument("--max-levels", type=int, default=6, help="depth: the largest depth tried")
+    ap.add_argument("--n", type=int, default=2048, help="orders, error_growth: the size n")
+    ap.add_argument("--dist", default="uniform", help="orders: input distribution")
+    ap.add_argument("--seed", type=int, default=11)
     ap.add_argument("--M", type=int, default=40000)
     ap.add_argument("--N", type=int, default=40000)
     ap.add_argument("--K", type=int, default=40000)
@@ -57,6 +195,12 @@ def main():
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     args = ap.parse_args()
+    if args.kernel == "depth":
+        return depth_study([int(x) for x in args.sizes.split(",")], args.max_levels)
+    if args.kernel == "orders":
+        return order_study(args.n, args.levels, args.dist, args.seed)
+    if args.kernel == "error_growth":
+        return error_growth(args.n)
 
     import torch
     from paper_1202_3173_amd import binding as sw
