@@ -162,6 +162,11 @@ int sw_plan_levels(int64_t n, int64_t budget_bytes);
 /* The modelled time in seconds behind sw_plan_levels for one depth (step order: the planner's for the
  * budget); -1.0 for bad arguments or when no step order of that depth fits.  Host arithmetic only. */
 double sw_model_seconds(int64_t n, int levels, int64_t budget_bytes);
+/* The same model for one explicit step order, with what the executor makes of `budget_bytes` of workspace (rich
+ * DFS steps; with overlap != 0 the second set of leaf-side buffers, whose additions then run beside the leaf
+ * products: a launch costs the longer of the two, the products stretched by 7 %).  -1.0 for bad arguments or
+ * when the order does not fit.  Host arithmetic only. */
+double sw_model_seconds_order(int64_t n, int levels, const char* schedule, int64_t budget_bytes, int overlap);
 
 /* ---- the planner (Section 3.1: pick the step order that uses the memory there is; Sections 3.3.1, 3.4.1) - */
 

@@ -17,7 +17,7 @@ EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",
            "sw_pre_add2", "sw_post_add2", "sw_leaf_gemm", "sw_pad_copy", "sw_profile_enable", "sw_profile_read",
            "sw_gemm_bilinear", "sw_plan_memory_bilinear", "sw_flop_count_bilinear", "sw_dgemm", "sw_plan_memory_dgemm",
-           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm", "sw_gemm_static", "sw_gemm_bilinear_levels", "sw_plan_memory_bilinear_levels")
+           "sw_plan_levels", "sw_model_seconds", "sw_gemm_rect", "sw_plan_memory_rect", "sw_trace_gemm", "sw_gemm_static", "sw_gemm_bilinear_levels", "sw_plan_memory_bilinear_levels", "sw_model_seconds_order")
 
 
 class SwError(RuntimeError):
@@ -58,6 +58,7 @@ def lib():
         "sw_plan_memory_dgemm": (i64, [ci, ci, i64, i64, i64, ci, cp]),
         "sw_plan_levels": (ci, [i64, i64]),
         "sw_model_seconds": (dbl, [i64, ci, i64]),
+        "sw_model_seconds_order": (dbl, [i64, ci, cp, i64, ci]),
         "sw_gemm_bilinear": (ci, [i64, vp, vp, vp, ci, cp, ci]),
         "sw_plan_memory_bilinear": (i64, [i64, ci, cp, ci]),
         "sw_flop_count_bilinear": (dbl, [i64, ci, ci]),
@@ -245,6 +246,10 @@ def sw_plan_levels(n, budget_bytes):
 
 def sw_model_seconds(n, levels, budget_bytes):
     return lib().sw_model_seconds(n, levels, int(budget_bytes))
+
+
+def sw_model_seconds_order(n, levels, schedule, budget_bytes, overlap=1):
+    return lib().sw_model_seconds_order(n, levels, _sched(schedule), int(budget_bytes), int(overlap))
 
 
 SW_SCHEME_WINOGRAD, SW_SCHEME_STRASSEN, SW_SCHEME_CLASSICAL, SW_SCHEME_LADERMAN, SW_SCHEME_CLASSICAL3 = 0, 1, 2, 3, 4

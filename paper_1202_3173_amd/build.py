@@ -2,6 +2,7 @@
 
   libsw_gemm.so    the product: planner, executor, kernels, C ABI (include/sw_gemm.h)
   libsw_inputs.so  the device-side synthetic input generator (not part of the product path)
+  libsw_probe.so   synthetic multi-stream copy kernels for the bandwidth sweep of kernel_bench (measurement only)
 
 hipcc cross-compiles without a GPU.  Flags: packed-FP32 code generation is switched off (the
 instructions are not trusted on the test machines); MFMA results stay in ordinary VGPRs
@@ -16,6 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsw_gemm.so")
 INPUTS_LIB = os.path.join(HERE, "libsw_inputs.so")
+PROBE_LIB = os.path.join(HERE, "libsw_probe.so")
 
 COMMON = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -35,6 +37,7 @@ def build(verbose=False):
     out = _run(COMMON + ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                          "-o", LIB] + [os.path.join(CSRC, s) for s in PRODUCT_SOURCES])
     out += _run(COMMON + ["-ffp-contract=off", "-o", INPUTS_LIB, os.path.join(CSRC, "inputs_fill.hip")])
+    out += _run(COMMON + ["-o", PROBE_LIB, os.path.join(CSRC, "hbm_probe.hip")])
     if verbose and out.strip():
         print(out)
     return LIB, INPUTS_LIB

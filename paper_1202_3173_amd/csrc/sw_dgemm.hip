@@ -119,21 +119,28 @@ double step_elems(Dims h, double a, double b, double c)
     return a * (double)h.m * (double)h.k + b * (double)h.k * (double)h.n + c * (double)h.m * (double)h.n;
 }
 
-double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich)
+// dbl: the buffers next to the leaves exist twice and additions run on their own streams (the three-stream
+// executor below a DFS step): the additions of the last BFS step (or fused pair) then run beside the leaf
+// products of the neighbouring launches, so a launch costs the longer of the two, with the products stretched
+// by the share of the machine's power the streaming kernels take (measured: 7 %).
+double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich, bool dbl)
 {
-    constexpr double HBM = 5.2e12, LAUNCH = 6e-6;
+    constexpr double HBM = 5.2e12, LAUNCH = 6e-6, STRETCH = 1.07;
     const Dims p{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)};
     double t = 0.0, parents = 1.0, launches = 1.0;   // `launches` subtrees in sequence, `parents` in each
+    double beside = 0.0;                             // additions per leaf launch that run beside the products
     Dims h = p;
     for (int i = 0; i < levels;) {
         h = h.half();
         if (fuse_two_bfs(order + i)) {
             h = h.half();
-            t += launches * (parents * 8.0 * step_elems(h, 65, 65, 65) / HBM + 3 * LAUNCH);
+            const double adds = parents * 8.0 * step_elems(h, 65, 65, 65) / HBM + 3 * LAUNCH;
+            if (dbl && i + 2 == levels) beside = adds; else t += launches * adds;
             parents *= 49.0;
             i += 2;
         } else if (order[i] == 'B') {
-            t += launches * (parents * 8.0 * step_elems(h, 11, 11, 11) / HBM + 3 * LAUNCH);
+            const double adds = parents * 8.0 * step_elems(h, 11, 11, 11) / HBM + 3 * LAUNCH;
+            if (dbl && i + 1 == levels) beside = adds; else t += launches * adds;
             parents *= 7.0;
             i += 1;
         } else {
@@ -144,22 +151,40 @@ double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich)
         }
     }
     // `parents` leaf products of shape h per launch, `launches` launches
-    t += launches * (parents * 2.0 * (double)h.m * (double)h.n * (double)h.k / leaf_rate((double)h.m, (double)h.n, (double)h.k, parents) + LAUNCH);
+    const double leaf = parents * 2.0 * (double)h.m * (double)h.n * (double)h.k / leaf_rate((double)h.m, (double)h.n, (double)h.k, parents) + LAUNCH;
+    if (beside > 0.0) {
+        const double both = leaf * STRETCH > beside ? leaf * STRETCH : beside;
+        t += launches * both + beside;               // the first launch's operands and the last one's fold are exposed
+    } else {
+        t += launches * leaf;
+    }
     if (p.m != d.m || p.n != d.n || p.k != d.k)
         t += 8.0 * ((double)d.m * d.k + (double)d.k * d.n + 2.0 * (double)d.m * d.n + (double)p.m * p.k + (double)p.k * p.n + 2.0 * (double)p.m * p.n) / HBM;
     return t;
+}
+double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich) { return modelled_seconds(d, levels, order, rich, false); }
+
+// the modelled time of one step order with what the executor would make of `budget` bytes of workspace
+// (rich DFS steps, second set of leaf-side buffers); -1.0 when the order does not fit
+double modelled_order_impl(Dims d, int levels, const char* order, int64_t budget, bool overlap, int odd_mode)
+{
+    if (levels == 0) return modelled_seconds(d, 0, order, 0, false);
+    const int64_t need = total_need(d, levels, order, odd_mode);
+    if (need > budget) return -1.0;
+    uint32_t rich = 0;
+    bool dbl = false;
+    const Dims p{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)};
+    const int64_t fixed = need - ws_need_bytes(p, order, 1);
+    choose_options(p, levels, order, budget - fixed, overlap, &rich, &dbl);
+    return modelled_seconds(d, levels, order, rich, dbl);
 }
 
 double modelled_for_budget(Dims d, int levels, int64_t budget, char* order)
 {
     if (levels == 0) { order[0] = '\0'; return modelled_seconds(d, 0, order, 0); }
-    if (plan(d, levels, budget, order) != SW_OK) return -1.0;       // no step order of this depth fits
-    uint32_t rich = 0;
-    bool dbl = false;
-    const Dims p{padded_n(d.m, levels), padded_n(d.n, levels), padded_n(d.k, levels)};
-    const int64_t fixed = total_need(d, levels, order) - ws_need_bytes(p, order, 1);
-    choose_options(p, levels, order, budget - fixed, false, &rich, &dbl);
-    return modelled_seconds(d, levels, order, rich);
+    const CallOpts o = current_opts();
+    if (plan(d, levels, budget, order, o.odd_mode, o.overlap != 0) != SW_OK) return -1.0;   // no step order of this depth fits
+    return modelled_order_impl(d, levels, order, budget, o.overlap != 0, o.odd_mode);
 }
 
 int best_levels(Dims d, int64_t budget)
@@ -346,6 +371,11 @@ int check_dims(int64_t M, int64_t N, int64_t K, int levels)
 
 }  // namespace
 
+double modelled_order(Dims d, int levels, const char* order, int64_t budget, bool overlap, int odd_mode)
+{
+    return modelled_order_impl(d, levels, order, budget, overlap, odd_mode);
+}
+
 int plan_levels(int64_t n, int64_t budget) { return n > 0 ? best_levels(n, budget) : 0; }
 
 }  // namespace sw
@@ -359,6 +389,12 @@ int sw_plan_levels(int64_t n, int64_t budget_bytes)
     if (n < 0 || n > 200000 || budget_bytes < 0) { set_error("bad argument"); return SW_EINVAL; }
     if (n == 0) return 0;
     return best_levels(n, budget_bytes);
+}
+
+double sw_model_seconds_order(int64_t n, int levels, const char* schedule, int64_t budget_bytes, int overlap)
+{
+    if (check_shape(n, levels) != SW_OK || n <= 0 || budget_bytes < 0 || !schedule || !schedule_ok(schedule, levels)) return -1.0;
+    return modelled_order_impl(Dims{n, n, n}, levels, schedule, budget_bytes, overlap != 0, SW_ODD_PAD);
 }
 
 double sw_model_seconds(int64_t n, int levels, int64_t budget_bytes)

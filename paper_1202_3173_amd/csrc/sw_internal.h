@@ -131,8 +131,10 @@ CallOpts current_opts();
 int64_t total_need(Dims d, int levels, const char* sched, int odd_mode);
 int64_t total_need(Dims d, int levels, const char* sched);                 // odd sizes as sw_set_odd_mode says now
 inline int64_t total_need(int64_t n, int levels, const char* sched) { return total_need(Dims{n, n, n}, levels, sched); }
-// the planner: most BFS steps that fit `budget`, then least memory; writes levels + 1 characters
-int plan(Dims d, int levels, int64_t budget, char* out, int odd_mode);
+// the planner: the best-scored Limited-Memory shape (DFS steps, then BFS steps) that fits `budget`; writes levels + 1 characters
+int plan(Dims d, int levels, int64_t budget, char* out, int odd_mode, bool overlap);
+// modelled seconds of one step order with what the executor makes of `budget` bytes; -1.0 if it does not fit
+double modelled_order(Dims d, int levels, const char* order, int64_t budget, bool overlap, int odd_mode);
 int plan(Dims d, int levels, int64_t budget, char* out);
 inline int plan(int64_t n, int levels, int64_t budget, char* out) { return plan(Dims{n, n, n}, levels, budget, out); }
 // the depth with the least modelled time among those some step order fits into `budget` bytes (0 < n <= 200000)

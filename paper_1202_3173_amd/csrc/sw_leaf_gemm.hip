@@ -53,28 +53,13 @@ struct GemmArgs {
     int accumulate;       // 0: C = A*B, 1: C += A*B
 };
 
-template <int VEC>
-__global__ void __launch_bounds__(NT, 2)
-leaf_gemm_kernel(const GemmArgs g)
+// One tile of C.  NI x NJ MFMA tiles of 16 x 16 per wavefront: the workgroup's 2 x 2 wavefronts cover
+// (32 NI) x (32 NJ) of the 128 x 128 grid cell, which is all of it for NI = NJ = 4 and the part that holds rows
+// and columns of the matrix for a cell on the bottom or right edge (NI, NJ = 2 or 3 when at most 64 or 96 of the
+// cell's rows / columns exist): an edge cell then issues NI NJ / 16 of the MFMAs of a full one.
+template <int VEC, int NI, int NJ>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, double* smem, const int batch, const int m0, const int n0)
 {
-    __shared__ __attribute__((aligned(16))) double smem[2 * STAGE];
-
-    // ---- which tile: XCD-aware remap, then grouped order inside a matrix ----
-    const int nb = gridDim.x;
-    const int bid = blockIdx.x;
-    const int xcd = bid % NUM_XCD;
-    const int per = nb / NUM_XCD, rem = nb % NUM_XCD;
-    const int logical = xcd * per + (xcd < rem ? xcd : rem) + bid / NUM_XCD;
-    const int tpm = g.tiles_m * g.tiles_n;
-    const int batch = logical / tpm;
-    const int t = logical - batch * tpm;
-    const int grp = t / (GROUP_M * g.tiles_n);
-    const int first_m = grp * GROUP_M;
-    const int gsz = min(GROUP_M, g.tiles_m - first_m);
-    const int tin = t - grp * (GROUP_M * g.tiles_n);
-    const int tile_m = first_m + tin % gsz;
-    const int tile_n = tin / gsz;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // uniform bases of this tile's A row panel and B column panel
     const double* __restrict__ A = g.A + (int64_t)batch * g.sa + (int64_t)m0 * g.lda;
@@ -170,30 +155,30 @@ leaf_gemm_kernel(const GemmArgs g)
     auto sstore = [&](int buf) __attribute__((always_inline)) { sstore_a(buf); sstore_b(buf); };
 
     // ---- fragments and accumulators -------------------------------------------------------------------------
-    v4d acc[4][4];
+    v4d acc[NI][NJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
+        for (int j = 0; j < NJ; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
 
-    double fa[2][4], fb[2][4];   // two fragment sets: one feeds the MFMAs while the other is being read
+    double fa[2][NI], fb[2][NJ];   // two fragment sets: one feeds the MFMAs while the other is being read
 
     // k-step s of the slab in buffer buf: lane (r16, g4) holds A[16 i + r16][4 s + g4] and B[4 s + g4][16 j + r16]
     auto fread = [&](int buf, int s, int set) __attribute__((always_inline)) {
-        const double* As = smem + buf * STAGE + (wm * 64 + r16) * SA + 4 * s + g4;
-        const double* Bs = smem + buf * STAGE + A_ELEMS + (4 * s + g4) * SB + wn * 64 + r16;
+        const double* As = smem + buf * STAGE + (wm * (16 * NI) + r16) * SA + 4 * s + g4;
+        const double* Bs = smem + buf * STAGE + A_ELEMS + (4 * s + g4) * SB + wn * (16 * NJ) + r16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[set][i] = As[i * 16 * SA];
+        for (int i = 0; i < NI; ++i) fa[set][i] = As[i * 16 * SA];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fb[set][j] = Bs[j * 16];
+        for (int j = 0; j < NJ; ++j) fb[set][j] = Bs[j * 16];
     };
 
     // MFMA tile rows i0 .. i1-1 of one k-step
     auto mfma_rows = [&](int set, int i0, int i1) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = i0; i < i1; ++i)
+        for (int i = i0; i < (i1 < NI ? i1 : NI); ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
     };
 #define SW_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -268,20 +253,72 @@ leaf_gemm_kernel(const GemmArgs g)
     }
 
     // ---- store: accumulator v of lane (r16, g4) in MFMA tile (i, j) is C[16 i + g4 + 4 v][16 j + r16] ----
+    const int row0 = m0 + wm * (16 * NI) + g4, col0 = n0 + wn * (16 * NJ) + r16;
+    if (!g.accumulate && m0 + 32 * NI <= g.M && n0 + 32 * NJ <= g.N) {
+        // the whole tile lies inside the matrix: one 64-bit address per lane, advanced by four rows per store
+        // group, the columns of a group as immediate offsets -- the fewer vector-ALU instructions here, the
+        // sooner the matrix pipe is handed to the next tile (each one queues behind the MFMAs of the other
+        // workgroup on this CU)
+        char* cp = reinterpret_cast<char*>(C + (int64_t)row0 * g.ldc + col0);
+        const int64_t step = 4 * g.ldc * (int64_t)sizeof(double);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) reinterpret_cast<double*>(cp)[j * 16] = acc[i][j][v];
+                cp += step;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int row = m0 + wm * 64 + i * 16 + g4 + 4 * v;
+            const int row = row0 + i * 16 + 4 * v;
             if (row < g.M) {
-                double* crow = C + (int64_t)row * g.ldc + n0 + wn * 64 + r16;
+                double* crow = C + (int64_t)row * g.ldc + col0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n0 + wn * 64 + j * 16 + r16 < g.N)
+                for (int j = 0; j < NJ; ++j)
+                    if (col0 + j * 16 < g.N)
                         crow[j * 16] = g.accumulate ? crow[j * 16] + acc[i][j][v] : acc[i][j][v];
             }
         }
     }
+}
+
+// how many 16-row (16-column) MFMA tiles per wavefront cover `left` remaining rows (columns) of a 128-wide cell
+__device__ __forceinline__ int wave_tiles(int left) { return left > 96 ? 4 : (left > 64 ? 3 : 2); }
+
+template <int VEC>
+__global__ void __launch_bounds__(NT, 2)
+leaf_gemm_kernel(const GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) double smem[2 * STAGE];
+
+    // ---- which tile: XCD-aware remap, then grouped order inside a matrix ----
+    const int nb = gridDim.x;
+    const int bid = blockIdx.x;
+    const int xcd = bid % NUM_XCD;
+    const int per = nb / NUM_XCD, rem = nb % NUM_XCD;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + bid / NUM_XCD;
+    const int tpm = g.tiles_m * g.tiles_n;
+    const int batch = logical / tpm;
+    const int t = logical - batch * tpm;
+    const int grp = t / (GROUP_M * g.tiles_n);
+    const int first_m = grp * GROUP_M;
+    const int gsz = min(GROUP_M, g.tiles_m - first_m);
+    const int tin = t - grp * (GROUP_M * g.tiles_n);
+    const int tile_m = first_m + tin % gsz;
+    const int tile_n = tin / gsz;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    // the shape of this cell's part of the matrix picks the body (uniform over the workgroup)
+    const int ni = wave_tiles(g.M - m0), nj = wave_tiles(g.N - n0);
+#define SW_TILE(I, J) if (ni == I && nj == J) { gemm_tile<VEC, I, J>(g, smem, batch, m0, n0); return; }
+    SW_TILE(4, 4) SW_TILE(4, 3) SW_TILE(3, 4) SW_TILE(3, 3) SW_TILE(4, 2) SW_TILE(2, 4) SW_TILE(3, 2) SW_TILE(2, 3) SW_TILE(2, 2)
+#undef SW_TILE
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -13,6 +13,8 @@
                                                                             # next to what sw_plan_levels picks
   python -m paper_1202_3173_amd.kernel_bench orders --n 16384 --levels 4     # whole product for every step order
                                                                             # that fits, next to the planner's pick
+  python -m paper_1202_3173_amd.kernel_bench streams --bytes 8589934592       # synthetic kernels with r input and w
+                                                                            # output streams: what HBM sustains
   python -m paper_1202_3173_amd.kernel_bench error_growth --n 2048           # error against the depth, with and
                                                                             # without diagonal scaling (Section 6.1)
 
@@ -127,6 +129,39 @@ def order_study(n, levels, dist, seed):
           f"{100.0 * (t_picked / best[1] - 1):.1f} % above the best)", flush=True)
 
 
+def stream_sweep(total_bytes, iters):
+    """The rate of one-pass streaming kernels against the number of streams read and written at once (16-byte
+    accesses, non-temporal, full grid), as a markdown table: bytes moved = (inputs + outputs) x stream length."""
+    import ctypes
+    import os
+    import torch
+    L = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsw_probe.so"))
+    L.sw_probe_streams.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                   ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream().cuda_stream
+    print("| streams in | streams out | GB per launch | ms | TB/s | of 8 TB/s |")
+    print("|---|---|---|---|---|---|")
+    for nin, nout in [(0, 1), (1, 0), (1, 1), (2, 1), (4, 1), (1, 4), (1, 8), (4, 4), (8, 8), (16, 16), (5, 3), (4, 7), (7, 4), (16, 49), (49, 16)]:
+        n2 = total_bytes // (nin + nout) // 16
+        n2 -= n2 % 4096
+        stride = n2 + 4096 + 16            # streams a little more than their length apart, never a power of two
+        a = torch.rand(max(nin, 1) * stride * 2, dtype=torch.float64, device=dev)
+        o = torch.empty(max(nout, 1) * stride * 2, dtype=torch.float64, device=dev)
+        blocks = min((n2 + 255) // 256, 1 << 20)
+
+        def launch():
+            rc = L.sw_probe_streams(nin, nout, a.data_ptr(), o.data_ptr(), n2, stride, stride, blocks, st)
+            assert rc == 0, rc
+        ms = _timed(launch, iters, 2)
+        moved = (nin + nout) * n2 * 16
+        rate = moved / (ms * 1e-3) / 1e12
+        print(f"| {nin} | {nout} | {moved / 1e9:.2f} | {ms:.3f} | {rate:.2f} | {100 * rate / 8.0:.0f} % |", flush=True)
+        del a, o
+        torch.cuda.empty_cache()
+
+
 def error_growth(n):
     """Markdown tables: the largest entry-wise error relative to ||A(i,:)|| ||B(:,j)|| (the quantity the scaled bound
     of Section 6.1 is stated in) in units of n*eps, and in brackets the norm-wise error in units of
@@ -172,7 +207,7 @@ def error_growth(n):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "copy", "dgemm", "depth", "orders", "error_growth"])
+    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "pre_add2", "post_add2", "copy", "dgemm", "depth", "orders", "streams", "error_growth"])
     ap.add_argument("--sizes", default="2048,4096,8192,16384,23520,32768,47040", help="depth: the sizes n")
     ap.add_argument("--max-levels", type=int, default=6, help="depth: the largest depth tried")
     ap.add_argument("--n", type=int, default=2048, help="orders, error_growth: the size n")
@@ -201,6 +236,8 @@ def main():
         return order_study(args.n, args.levels, args.dist, args.seed)
     if args.kernel == "error_growth":
         return error_growth(args.n)
+    if args.kernel == "streams":
+        return stream_sweep(args.bytes, args.iters)
 
     import torch
     from paper_1202_3173_amd import binding as sw
@@ -242,6 +279,23 @@ def main():
                "levels": args.levels if args.levels >= 0 else "auto (block shape and depth by the library's cost model)",
                "avg_ms": round(ms, 3), "achieved": round(eff, 2), "unit": "effective TFLOP/s (2MNK/t)",
                "peak": FP64_MFMA_PEAK_TFLOPS, "frac": round(eff / FP64_MFMA_PEAK_TFLOPS, 4), "bound": "mfma"}
+    elif args.kernel in ("pre_add2", "post_add2"):
+        m, live = args.h, args.live                 # --h is the grandchild size here: the parent is 4 m x 4 m
+        n = 4 * m
+        ld = pitch(m)
+        cs = (ld * m + 31) // 32 * 32
+        pld = pitch(n)
+        ps = (pld * n + 31) // 32 * 32
+        P = torch.rand(live * ps, dtype=torch.float64, device=dev)
+        K = torch.rand(live * 49 * cs, dtype=torch.float64, device=dev)
+        if args.kernel == "pre_add2":
+            ms = _timed(lambda: sw.sw_pre_add2(args.side, P, pld, ps, live, m, K, ld, cs), args.iters, args.warmup)
+        else:
+            ms = _timed(lambda: sw.sw_post_add2(K, ld, cs, live, m, P, pld, ps), args.iters, args.warmup)
+        nbytes = 8.0 * live * m * m * 65
+        rate = nbytes / (ms * 1e-3) / 1e9
+        out = {"kernel": args.kernel, "m": m, "live": live, "avg_ms": round(ms, 4), "GBps": round(rate, 1),
+               "frac_of_hbm_peak": round(rate / HBM_PEAK_GBPS, 4)}
     elif args.kernel in ("pre_add", "post_add"):
         h, live = args.h, args.live
         n = 2 * h

@@ -97,6 +97,34 @@ def test_planner_prefers_bfs_and_puts_dfs_first():
             assert "BD" not in s            # DFS steps first (Limited-Memory shape)
 
 
+def test_planner_picks_on_the_measured_sizes():
+    """The planner's choice at the sizes where every step order was timed on the MI355X (profiles/step_orders.md):
+    each pick below is the fastest measured order or within 0.3 % of it.  Only Limited-Memory shapes (DFS steps,
+    then BFS steps; Section 3.4) are ever picked."""
+    free = 290 << 30
+    for n, L, want in [(4096, 3, "BBB"), (8192, 3, "DBB"), (8192, 4, "DBBB"), (16384, 4, "DDBB"), (23520, 5, "DBBBB"),
+                       (32768, 4, "DDBB"), (47040, 4, "DDBB"), (94080, 5, "DDDBB")]:
+        assert sw.sw_plan_schedule(n, L, free - 3 * n * n * 8) == want, (n, L)
+    for n in (300, 1000, 5000, 20000, 70000):
+        for L in range(1, 6):
+            if (n >> L) < 16:
+                continue
+            for budget in (sw.sw_plan_memory(n, L, None), 10 ** 9, 10 ** 10, 10 ** 11):
+                if budget < sw.sw_plan_memory(n, L, None):
+                    continue
+                s = sw.sw_plan_schedule(n, L, budget)
+                assert "BD" not in s and sw.sw_plan_memory(n, L, s) <= budget
+    # one stream: nothing runs beside the leaf products, the all-BFS order wins where it fits
+    sw.sw_set_overlap(0)
+    try:
+        assert sw.sw_plan_schedule(16384, 4, free) == "BBBB"
+    finally:
+        sw.sw_set_overlap(1)
+    # the model behind the choice: an order that does not fit has no time, one that fits has a positive one
+    assert sw.sw_model_seconds_order(94080, 5, "DDBBB", int(50e9)) == -1.0
+    assert 10.0 < sw.sw_model_seconds_order(94080, 5, "DDDBB", int(81e9)) < 16.0
+
+
 def test_plan_workspace_spends_extra_memory_on_the_deepest_dfs_steps():
     def elems(h):
         ld = (h + 15) // 16 * 16
