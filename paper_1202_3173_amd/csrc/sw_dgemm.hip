@@ -106,7 +106,9 @@ double leaf_rate(double m, double n, double k, double batch)
     // 512 workgroup slots (two per CU) are filled in rounds; a last round of at most 256 tiles has every CU
     // to one workgroup, which then runs at 0.89 of the rate of two and finishes in 0.56 of a round
     const double full = floor(tiles / 512.0), rest = tiles - 512.0 * full;
-    const double rounds = full + (rest == 0.0 ? 0.0 : (rest <= 256.0 ? 0.56 : 1.0));
+    // (after full rounds the slots free up one by one, so a short rest costs less than a whole lone-workgroup tile)
+    const double lone = (full > 0.0 && rest / 512.0 + 0.25 < 0.56) ? rest / 512.0 + 0.25 : 0.56;
+    const double rounds = full + (rest == 0.0 ? 0.0 : (rest <= 256.0 ? lone : 1.0));
     return table_rate(k) * 1e12 * fill * (tiles / 512.0) / rounds;
 }
 

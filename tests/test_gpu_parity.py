@@ -348,6 +348,38 @@ def test_three_stream_overlap_gives_the_same_bits_as_one_stream(oracle, n, level
         assert np.array_equal(val, first), key
 
 
+def test_two_host_threads_with_distinct_workspaces_and_streams():
+    """Two host threads inside sw_gemm_ex at once (ctypes drops the interpreter lock during the call), each with its
+    own operands, workspace and stream, many times over: every call takes its own internal streams and events, so
+    the results are the ones each thread gets alone (exact products of integer-valued inputs)."""
+    import threading
+    jobs = []
+    for k, (n, levels, sched) in enumerate([(1536, 3, "DDB"), (1280, 3, "DBB")]):
+        A, B = inputs.device_pair(dict(n=n, seed=60 + k, dist="integer"), DEV)
+        C = torch.empty((n, n), dtype=torch.float64, device=DEV)
+        ws = torch.empty(sw.sw_plan_workspace(n, levels, sched, 1 << 33), dtype=torch.uint8, device=DEV)
+        jobs.append(dict(n=n, levels=levels, sched=sched, A=A, B=B, C=C, ws=ws, stream=torch.cuda.Stream(), want=A @ B, bad=[]))
+    torch.cuda.synchronize()
+    go = threading.Barrier(2)
+
+    def work(j):
+        go.wait()
+        for rep in range(12):
+            j["C"].fill_(float("nan"))
+            torch.cuda.synchronize()
+            sw.sw_gemm_ex(j["n"], j["A"], j["n"], j["B"], j["n"], j["C"], j["n"], j["levels"], j["sched"], j["ws"], j["stream"].cuda_stream)
+            j["stream"].synchronize()
+            if not torch.equal(j["C"], j["want"]):
+                j["bad"].append(rep)
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert [j["bad"] for j in jobs] == [[], []]
+
+
 def test_product_can_be_captured_in_a_hip_graph_and_replayed(oracle):
     # the library allocates nothing, records no memset and never synchronises, so a caller may capture it;
     # every replay, with eager work of the program in between, must reproduce the eager result
