@@ -245,11 +245,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, double* smem, const
         slab(kt, 0, true, 1);
         slab(kt + 1, 1, true, 1);
     }
-    // the last (up to four) slabs: nothing more to store or load at the very end, and a ragged K tail
-    for (; kt < KT; ++kt) {
-        const bool store = kt + 1 < KT;
-        const int load = kt + 2 < KT ? ((ragged && kt + 2 == KT - 1) ? 2 : 1) : 0;
-        slab(kt, kt & 1, store, load);
+    // the last (up to four) slabs: nothing more to store or load at the very end, and a ragged K tail.  Two per
+    // trip as well (kt is even here), so the buffers stay compile-time constants and only the flags are decided
+    // at run time, by scalar branches: with the buffer a run-time value every LDS access of these slabs needed
+    // vector-ALU address arithmetic, and they took twice as long as steady ones.
+    auto last_slab = [&](int k, auto buf) __attribute__((always_inline)) {
+        const bool store = k + 1 < KT;
+        const int load = k + 2 < KT ? ((ragged && k + 2 == KT - 1) ? 2 : 1) : 0;
+        slab(k, decltype(buf)::value, store, load);
+    };
+    for (; kt < KT; kt += 2) {
+        last_slab(kt, std::integral_constant<int, 0>());
+        if (kt + 1 < KT) last_slab(kt + 1, std::integral_constant<int, 1>());
     }
 
     // ---- store: accumulator v of lane (r16, g4) in MFMA tile (i, j) is C[16 i + g4 + 4 v][16 j + r16] ----
