@@ -76,7 +76,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default cfg5, the metric's configuration)")
-    ap.add_argument("--schedule", default=None, help="override the step order (default: the configuration's, or the planner's)")
+    ap.add_argument("--schedule", default=None, help="override the step order: B/D characters, or `planner` for the planner's pick "
+                                                        "(default: the configuration's, or the planner's where it names none)")
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
     ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
@@ -135,7 +136,7 @@ def main():
     for x in (per_level or [sw.SW_SCHEME_WINOGRAD] * levels):
         radix *= sw.SCHEME_BASE[x]
     if scheme == sw.SW_SCHEME_WINOGRAD:
-        schedule = args.schedule or cfg["schedule"] or sw.sw_plan_schedule(n, levels, budget)
+        schedule = (None if args.schedule == "planner" else args.schedule or cfg["schedule"]) or sw.sw_plan_schedule(n, levels, budget)
         if levels == 0:
             schedule = ""
         need = sw.sw_plan_workspace(n, levels, schedule, budget)   # the minimum plus what the library can use
