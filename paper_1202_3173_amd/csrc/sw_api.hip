@@ -442,6 +442,7 @@ struct Exec {
     void op(int s, int cls, double work, std::initializer_list<Range> reads, std::initializer_list<Range> writes, F&& launch)
     {
         if (err != hipSuccess) return;
+        if (reads.size() > 8 || writes.size() > 8) { err = hipErrorInvalidValue; return; }
         Range rd[8], wr[8];
         int nr = 0, nw = 0;
         for (const Range& r : reads) if (declared++ != withhold) rd[nr++] = r;
@@ -1097,6 +1098,7 @@ int sw_profile_read(double* ms, int64_t* launches, double* work)
     if (!ms || !launches || !work) { set_error("NULL output"); return SW_EINVAL; }
     for (int i = 0; i < SW_NUM_CLASSES; ++i) { ms[i] = 0.0; launches[i] = 0; work[i] = 0.0; }
     hipError_t bad = hipSuccess;
+    std::lock_guard<std::mutex> guard(g_prof.mu);
     for (auto& r : g_prof.recs) {
         if (r.e0 && r.e1) {
             float t = 0.f;
