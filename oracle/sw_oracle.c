@@ -248,6 +248,92 @@ int sw_oracle_gemm(int64_t n, const double *A, const double *B, double *C, int l
     return sw_oracle_gemm_table(n, A, B, C, levels, 0);
 }
 
+/* ---- dynamic peeling (Section 3.1 names it beside padding) ---------------- */
+
+/* The same recursion for any n >= 2^levels without padding: whenever the size
+ * at some level is odd, the last row and column are peeled off, the step is
+ * taken on the leading even block, and the peeled parts are finished by their
+ * definitions:
+ *   C11 += a12 * b21            (column of A times row of B, one term more)
+ *   c12  = [A11 a12] * [b12; b22]   (last column of C, rows above the last)
+ *   [c21 c22] = [a21 a22] * B       (last row of C)
+ * each sum in ascending k, multiply then add.  The children of the even block
+ * have half its size and may be odd again ("dynamic": decided level by level). */
+static int sw_rec_peel(const double *A, int64_t lda, const double *B, int64_t ldb,
+                       double *C, int64_t ldc, int64_t n, int levels)
+{
+    if (levels == 0) {
+        classical(A, lda, B, ldb, C, ldc, n);
+        return 0;
+    }
+    if (n % 2 == 1) {
+        const int64_t m = n - 1;
+        int rc = sw_rec_peel(A, lda, B, ldb, C, ldc, m, levels);   /* C11 = A11 * B11 */
+        if (rc != 0) return rc;
+        for (int64_t i = 0; i < m; ++i) {
+            const double a = A[i * lda + m];
+            for (int64_t j = 0; j < m; ++j) C[i * ldc + j] = C[i * ldc + j] + a * B[m * ldb + j];
+            double s = A[i * lda] * B[m];                           /* column m of B */
+            for (int64_t k = 1; k < n; ++k) s = s + A[i * lda + k] * B[k * ldb + m];
+            C[i * ldc + m] = s;
+        }
+        for (int64_t j = 0; j < n; ++j) {
+            double s = A[m * lda] * B[j];
+            for (int64_t k = 1; k < n; ++k) s = s + A[m * lda + k] * B[k * ldb + j];
+            C[m * ldc + j] = s;
+        }
+        return 0;
+    }
+    const int64_t h = n / 2;
+    const double *A11 = A, *A12 = A + h, *A21 = A + h * lda, *A22 = A + h * lda + h;
+    const double *B11 = B, *B12 = B + h, *B21 = B + h * ldb, *B22 = B + h * ldb + h;
+    double *C11 = C, *C12 = C + h, *C21 = C + h * ldc, *C22 = C + h * ldc + h;
+    const size_t hh = (size_t)h * (size_t)h;
+    double *buf = (double *)malloc(18 * hh * sizeof(double));
+    if (!buf) return -1;
+    double *T2 = buf, *T3 = T2 + hh, *T4 = T3 + hh, *T5 = T4 + hh;
+    double *S2 = T5 + hh, *S3 = S2 + hh, *S4 = S3 + hh, *S6 = S4 + hh;
+    double *Q[7];
+    for (int i = 0; i < 7; ++i) Q[i] = S6 + hh + (size_t)i * hh;
+    double *U1 = Q[6] + hh, *U2 = U1 + hh, *U3 = U2 + hh;
+    /* Appendix A with the corrected tokens, as in sw_rec */
+    madd(T2, h, A21, lda, A22, lda, h, +1);
+    madd(T3, h, T2, h, A11, lda, h, -1);
+    madd(T4, h, A11, lda, A21, lda, h, -1);
+    madd(T5, h, A12, lda, T3, h, h, -1);
+    madd(S2, h, B12, ldb, B11, ldb, h, -1);
+    madd(S3, h, B22, ldb, S2, h, h, -1);
+    madd(S4, h, B22, ldb, B12, ldb, h, -1);
+    madd(S6, h, S3, h, B21, ldb, h, -1);
+    const double *T[7] = {A11, A12, T2, T3, T4, T5, A22};
+    const int64_t ldt[7] = {lda, lda, h, h, h, h, lda};
+    const double *S[7] = {B11, B21, S2, S3, S4, B22, S6};
+    const int64_t lds[7] = {ldb, ldb, h, h, h, ldb, h};
+    int rc = 0;
+    for (int i = 0; i < 7 && rc == 0; ++i) rc = sw_rec_peel(T[i], ldt[i], S[i], lds[i], Q[i], h, h, levels - 1);
+    if (rc == 0) {
+        madd(U1, h, Q[0], h, Q[3], h, h, +1);
+        madd(U2, h, U1, h, Q[4], h, h, +1);
+        madd(U3, h, U1, h, Q[2], h, h, +1);
+        madd(C11, ldc, Q[0], h, Q[1], h, h, +1);
+        madd(C12, ldc, U3, h, Q[5], h, h, +1);
+        madd(C21, ldc, U2, h, Q[6], h, h, -1);
+        madd(C22, ldc, U2, h, Q[2], h, h, +1);
+    }
+    free(buf);
+    return rc;
+}
+
+/* C = A*B with `levels` Strassen-Winograd steps and peeling at every level whose
+ * size is odd; n >= 2^levels.  Returns 0, -1 on allocation failure, -2 on bad arguments. */
+int sw_oracle_gemm_peel(int64_t n, const double *A, const double *B, double *C, int levels)
+{
+    if (n < 0 || levels < 0 || levels > 30 || (n > 0 && (!A || !B || !C))) return -2;
+    if (n == 0) return 0;
+    if (((int64_t)1 << levels) > n) return -2;
+    return sw_rec_peel(A, n, B, n, C, n, n, levels);
+}
+
 /* ---- memory of a traversal (Sections 3.3.1 and 3.4.1) --------------------- */
 
 /* Peak number of words of S/T/Q storage, beyond A, B and C, that a traversal

@@ -36,6 +36,8 @@ def lib():
         L.sw_oracle_gemm.restype = ctypes.c_int
         L.sw_oracle_gemm_table.argtypes = [ctypes.c_int64, dp, dp, dp, ctypes.c_int, ctypes.c_int]
         L.sw_oracle_gemm_table.restype = ctypes.c_int
+        L.sw_oracle_gemm_peel.argtypes = [ctypes.c_int64, dp, dp, dp, ctypes.c_int]
+        L.sw_oracle_gemm_peel.restype = ctypes.c_int
         L.sw_oracle_naive.argtypes = [ctypes.c_int64, dp, dp, dp]
         L.sw_oracle_naive.restype = None
         L.sw_oracle_entry.argtypes = [ctypes.c_int64, dp, dp, ctypes.c_int64]
@@ -78,6 +80,20 @@ def gemm(A, B, levels, table=0):
     rc = lib().sw_oracle_gemm_table(n, _ptr(A), _ptr(B), _ptr(C), int(levels), int(table))
     if rc != 0:
         raise RuntimeError(f"sw_oracle_gemm_table failed with {rc}")
+    return C
+
+
+def gemm_peel(A, B, levels):
+    """C = A @ B by `levels` Strassen-Winograd steps with the last row and column peeled off at every level whose size
+    is odd (no padding); needs n >= 2^levels."""
+    A = _square(A, "A")
+    B = _square(B, "B")
+    if A.shape != B.shape:
+        raise ValueError("A and B differ in size")
+    C = np.empty_like(A)
+    rc = lib().sw_oracle_gemm_peel(A.shape[0], _ptr(A), _ptr(B), _ptr(C), int(levels))
+    if rc != 0:
+        raise RuntimeError(f"sw_oracle_gemm_peel failed with {rc}")
     return C
 
 

@@ -12,6 +12,9 @@ wrong sign or quadrant, a transposed operand, a wrong count) fails it:
   * the tables exactly as printed are shown NOT to give a product (reading R1);
   * floating-point results against an extended-precision product, inside the
     norm-wise bound form of Section 6.1;
+  * the recursion with peeling at every odd level: exact integers at sizes that
+    are odd at one, several or all levels, bit equality with the plain recursion
+    when no level is odd, asymmetric operands;
   * row and column strips of the definition (used to referee large results):
     exact integers against a pure-Python brute force and int64 matmul, bit
     equality with the same rows / columns of the whole naive product, and
@@ -254,6 +257,42 @@ def test_float_result_close_to_extended_precision_product(oracle, dist):
     # levels = 0 obeys the tighter component-wise bound n*eps*|A||B| of the classical algorithm
     comp = n * np.finfo(float).eps * (np.abs(A) @ np.abs(B))
     assert np.all(np.abs(oracle.gemm(A, B, 0) - ref) <= comp)
+
+
+# ---- peeling at every odd level ----------------------------------------------------
+
+@pytest.mark.parametrize("n,levels", [(3, 1), (5, 1), (5, 2), (7, 2), (9, 3), (11, 2), (13, 3), (21, 4), (22, 3), (37, 5), (16, 3), (100, 5), (127, 6)])
+def test_peeled_recursion_is_exact_on_integers(oracle, n, levels):
+    """Sizes that are odd at one, several or all levels (127 = 2^7 - 1 is odd at every level; 22 -> 11 -> 5 -> 2 mixes):
+    integer inputs must give the exact product, against a pure-Python brute force for the small ones."""
+    A, B = int_pair(n, 500 + n)
+    C = oracle.gemm_peel(A, B, levels)
+    assert np.array_equal(C, (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64))
+    if n <= 13:
+        assert C.tolist() == [[float(v) for v in row] for row in brute(A.tolist(), B.tolist())]
+
+
+def test_peeled_recursion_special_cases(oracle):
+    # an even size at every level is the plain recursion, bit for bit; no level is the classical product
+    for n, levels in ((16, 3), (48, 4), (40, 3)):
+        A = inputs.matrix(n, 3, 0, "uniform")
+        B = inputs.matrix(n, 3, 1, "uniform")
+        assert np.array_equal(oracle.gemm_peel(A, B, levels), oracle.gemm(A, B, levels))
+    A = inputs.matrix(33, 4, 0, "uniform")
+    B = inputs.matrix(33, 4, 1, "uniform")
+    assert np.array_equal(oracle.gemm_peel(A, B, 0), oracle.naive(A, B))
+    # asymmetric operands: not B*A, not a transpose; and floats stay inside the tolerance of the padded recursion
+    n = 45
+    A = np.arange(1.0, n * n + 1).reshape(n, n) % 17 - 8
+    B = np.triu(np.ones((n, n))) * (np.arange(n)[None, :] % 5 - 2)
+    ref = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    assert not np.array_equal(ref, B @ A) and np.array_equal(oracle.gemm_peel(A, B, 3), ref)
+    Af = inputs.matrix(77, 9, 0, "uniform")
+    Bf = inputs.matrix(77, 9, 1, "rowscaled")
+    exact = (Af.astype(np.longdouble) @ Bf.astype(np.longdouble)).astype(np.float64)
+    assert np.max(np.abs(oracle.gemm_peel(Af, Bf, 4) - exact)) <= 1e-10 * 77 * np.max(np.abs(Af)) * np.max(np.abs(Bf))
+    with pytest.raises(RuntimeError):
+        oracle.gemm_peel(Af[:7, :7], Bf[:7, :7], 3)          # 2^levels exceeds n
 
 
 # ---- strips of the definition ----------------------------------------------------
