@@ -80,7 +80,8 @@ def main():
                                                         "(default: the configuration's, or the planner's where it names none)")
     ap.add_argument("--n", type=int, default=None, help="override the configuration's n (other sizes than the five)")
     ap.add_argument("--levels", type=int, default=None, help="override the number of levels (0 = the classical MFMA product)")
-    ap.add_argument("--odd-mode", choices=["pad", "peel"], default="pad", help="when 2^levels does not divide n")
+    ap.add_argument("--odd-mode", choices=["pad", "peel", "peel-levels"], default="pad",
+                    help="when 2^levels does not divide n: zero-padded copies, one peel at the top, or a peel at every odd level")
     ap.add_argument("--overlap", type=int, default=None, help="0: one stream; 1 (default): three streams, leaf-side addition kernels sized to their work; k > 1: capped at k workgroups")
     ap.add_argument("--scheme", default="winograd",
                     help="the block scheme under the recursion (Section 6.6): winograd (default, the Strassen-Winograd path), strassen, "
@@ -105,7 +106,7 @@ def main():
         cfg.update(n=args.n, name=f"{cfg['name']} with n={args.n}", schedule=None)
     if args.levels is not None:
         cfg.update(levels=args.levels, name=f"{cfg['name']} with levels={args.levels}", schedule=None)
-    sw.sw_set_odd_mode(sw.SW_ODD_PEEL if args.odd_mode == "peel" else sw.SW_ODD_PAD)
+    sw.sw_set_odd_mode({"pad": sw.SW_ODD_PAD, "peel": sw.SW_ODD_PEEL, "peel-levels": sw.SW_ODD_PEEL_LEVELS}[args.odd_mode])
     if args.overlap is not None:
         sw.sw_set_overlap(args.overlap)
     n, levels = cfg["n"], cfg["levels"]

@@ -11,7 +11,7 @@ SW_OK, SW_EINVAL, SW_ENOMEM, SW_EHIP = 0, -1, -2, -3
 SW_MAX_LEVELS = 16
 CLASS_NAMES = ("pre_add", "post_add", "leaf_gemm", "dfs_add", "pad", "peel", "scale", "blas")
 SW_SCALE_OUTSIDE, SW_SCALE_INSIDE = 1, 2
-SW_ODD_PAD, SW_ODD_PEEL = 0, 1
+SW_ODD_PAD, SW_ODD_PEEL, SW_ODD_PEEL_LEVELS = 0, 1, 2
 
 EXPORTS = ("sw_gemm", "sw_gemm_ex", "sw_gemm_scaled", "sw_plan_memory_scaled", "sw_plan_memory", "sw_plan_workspace", "sw_plan_schedule", "sw_model_words", "sw_lm_dfs_steps",
            "sw_flop_count", "sw_set_workspace", "sw_set_stream", "sw_set_odd_mode", "sw_set_overlap", "sw_gemm_classical", "sw_last_error", "sw_pre_add", "sw_post_add",

@@ -150,6 +150,8 @@ int64_t total_need(Dims d, int levels, const char* sched, int odd_mode)
     if (d.m == 0 || d.n == 0 || d.k == 0) return 0;
     // peeling: the recursion runs in place on the previous multiples of 2^levels, no copies
     if (odd_mode == SW_ODD_PEEL) return ws_need_bytes(floor_dims(d, levels), sched, 1);
+    // peeling level by level: in place on the extents as they are (every step halves them, rounding down)
+    if (odd_mode == SW_ODD_PEEL_LEVELS) return ws_need_bytes(d, sched, 1);
     const Dims p = padded_dims(d, levels);
     int64_t bytes = ws_need_bytes(p, sched, 1);
     if (p.m != d.m || p.n != d.n || p.k != d.k)
@@ -171,7 +173,7 @@ int plan(Dims d, int levels, int64_t budget, char* out, int odd_mode, bool overl
     struct Cand { char s[SW_MAX_LEVELS + 1]; double t; bool paired, full; };
     Cand cand[SW_MAX_LEVELS + 1];
     int nc = 0;
-    const Dims p = odd_mode == SW_ODD_PEEL ? floor_dims(d, levels) : padded_dims(d, levels);
+    const Dims p = odd_mode == SW_ODD_PEEL ? floor_dims(d, levels) : (odd_mode == SW_ODD_PEEL_LEVELS ? d : padded_dims(d, levels));
     for (int l = 0; l <= levels; ++l) {
         Cand c;
         for (int i = 0; i < levels; ++i) c.s[i] = i < l ? 'D' : 'B';
@@ -400,6 +402,7 @@ struct Exec {
     bool bg = false;              // the operations being issued are the leaf-side ones of a double-buffered step
     Profiler* prof;
     hipError_t err = hipSuccess;
+    bool peel_levels = false;     // SW_ODD_PEEL_LEVELS: peel the odd row / column / inner index at every level
     int64_t declared = 0;         // ranges declared to the dependency tracker so far
     int64_t withhold = -1;        // record-only runs: the number of ONE declared range to keep from the tracker (a
                                   // planted mistake, which the checker of the record must then find); -1: none
@@ -491,10 +494,34 @@ struct Exec {
                [&](hipStream_t st) { return launch_gemm(d.m, d.n, d.k, live, A, B, C, false, st); });
             return;
         }
+        if (peel_levels && ((d.m | d.n | d.k) & 1)) {
+            // Peeling at this level (Section 3.1, "dynamic peeling"): the step runs on the leading even extents, in
+            // place; the last row, column and inner index of all `live` problems are finished by thin classical
+            // products on the MFMA kernel.  Behind every row of the even part lies the peeled element.
+            const Dims e{d.m & ~(int64_t)1, d.n & ~(int64_t)1, d.k & ~(int64_t)1};
+            const int64_t rm = d.m - e.m, rn = d.n - e.n, rk = d.k - e.k;
+            Mat Ae = A, Be = B, Ce = C;
+            Ae.padded = A.padded || rk;
+            Be.padded = B.padded || rn;
+            Ce.padded = C.padded || rn;
+            mul(Ae, Be, Ce, e, level, live);                             // C11  = A11 * B11
+            const Mat a12{A.p + e.k, A.ld, A.stride, A.padded}, b21{B.p + e.k * B.ld, B.ld, B.stride, B.padded};
+            const Mat bright{B.p + e.n, B.ld, B.stride, B.padded}, c12{C.p + e.n, C.ld, C.stride, C.padded};
+            const Mat abot{A.p + e.m * A.ld, A.ld, A.stride, A.padded}, cbot{C.p + e.m * C.ld, C.ld, C.stride, C.padded};
+            op(S_POST, SW_CLASS_PEEL,
+               2.0 * live * ((double)e.m * e.n * rk + (double)e.m * rn * d.k + (double)rm * d.n * d.k),
+               {rng(A, d.m, d.k, live), rng(B, d.k, d.n, live)}, {rng(C, d.m, d.n, live)}, [&](hipStream_t st) {
+                   hipError_t e1 = rk ? launch_gemm(e.m, e.n, rk, live, a12, b21, Ce, true, st) : hipSuccess;        // C11 += a12 * b21
+                   hipError_t e2 = rn ? launch_gemm(e.m, rn, d.k, live, A, bright, c12, false, st) : hipSuccess;     // c12  = [A11 a12] * [b12; b22]
+                   hipError_t e3 = rm ? launch_gemm(rm, d.n, d.k, live, abot, B, cbot, false, st) : hipSuccess;      // [c21 c22] = [a21 a22] * B
+                   return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
+               });
+            return;
+        }
         const Dims h = d.half();
         const int64_t eT = ws_mat_elems(h.m, h.k), eS = ws_mat_elems(h.k, h.n), eQ = ws_mat_elems(h.m, h.n);
         const int64_t mark = used;
-        const bool fused = fuse_two_bfs(sched + level);
+        const bool fused = fuse_here(d, sched + level);
         const Dims q = h.half();
         const int64_t e4T = ws_mat_elems(q.m, q.k), e4S = ws_mat_elems(q.k, q.n), e4Q = ws_mat_elems(q.m, q.n);
         // the step whose children are the leaves: with two sets of buffers, consecutive launches alternate
@@ -663,7 +690,9 @@ int gemm_rect_impl(Dims d, const double* A, int64_t lda, const double* B, int64_
     ex.levels = levels;
     const Dims lead = floor_dims(d, levels);
     const bool peel = opts.odd_mode == SW_ODD_PEEL && (lead.m != d.m || lead.n != d.n || lead.k != d.k);
-    const Dims rec = peel ? lead : padded_dims(d, levels);
+    const bool peel_levels = opts.odd_mode == SW_ODD_PEEL_LEVELS;
+    const Dims rec = peel ? lead : (peel_levels ? d : padded_dims(d, levels));
+    ex.peel_levels = peel_levels;
     {
         // spend what the workspace has beyond the minimum: first on a second set of the buffers next to the
         // leaves (so that additions and leaf products of consecutive launches overlap), then on the rich form
@@ -765,7 +794,7 @@ int64_t sw_trace_gemm(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
                       int64_t workspace_bytes, int overlap, int odd_mode, int64_t withhold, int64_t* log, int64_t log_words)
 {
     if (workspace_bytes < 0 || M < 0 || N < 0 || K < 0 || log_words < 0 || overlap < 0) { set_error("negative argument"); return SW_EINVAL; }
-    if (odd_mode != SW_ODD_PAD && odd_mode != SW_ODD_PEEL) { set_error("unknown mode %d", odd_mode); return SW_EINVAL; }
+    if (odd_mode != SW_ODD_PAD && odd_mode != SW_ODD_PEEL && odd_mode != SW_ODD_PEEL_LEVELS) { set_error("unknown mode %d", odd_mode); return SW_EINVAL; }
     // synthetic operand addresses, 2^40 bytes apart (no matrix the library accepts is that large)
     const uintptr_t T = (uintptr_t)1 << 40;
     Tracer t;
@@ -897,7 +926,8 @@ int64_t sw_plan_workspace(int64_t n, int levels, const char* schedule, int64_t b
     }
     if (n == 0) return 0;
     const int64_t q = (int64_t)1 << levels;
-    const int64_t nrec = (n % q && g_odd_mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels);
+    const int mode = g_odd_mode.load();
+    const int64_t nrec = mode == SW_ODD_PEEL_LEVELS ? n : ((n % q && mode == SW_ODD_PEEL) ? n - n % q : padded_n(n, levels));
     const int64_t fixed = need - ws_need_bytes(nrec, schedule, 1);
     uint32_t rich = 0;
     bool dbl = false;
@@ -968,7 +998,7 @@ int sw_set_overlap(int on)
 
 int sw_set_odd_mode(int mode)
 {
-    if (mode != SW_ODD_PAD && mode != SW_ODD_PEEL) { set_error("unknown mode %d", mode); return SW_EINVAL; }
+    if (mode != SW_ODD_PAD && mode != SW_ODD_PEEL && mode != SW_ODD_PEEL_LEVELS) { set_error("unknown mode %d", mode); return SW_EINVAL; }
     g_odd_mode = mode;
     return SW_OK;
 }

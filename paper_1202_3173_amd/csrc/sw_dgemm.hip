@@ -133,8 +133,9 @@ double modelled_seconds(Dims d, int levels, const char* order, uint32_t rich, bo
     double beside = 0.0;                             // additions per leaf launch that run beside the products
     Dims h = p;
     for (int i = 0; i < levels;) {
+        const Dims cur = h;
         h = h.half();
-        if (fuse_two_bfs(order + i)) {
+        if (fuse_here(cur, order + i)) {
             h = h.half();
             const double adds = parents * 8.0 * step_elems(h, 65, 65, 65) / HBM + 3 * LAUNCH;
             if (dbl && i + 2 == levels) beside = adds; else t += launches * adds;

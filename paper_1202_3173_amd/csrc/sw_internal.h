@@ -44,6 +44,15 @@ inline bool fuse_two_bfs(const char* sched)
     return run >= 2 && run % 2 == 0;
 }
 
+// ... and only when the level between the two steps has even extents: with peeling at every odd level
+// (SW_ODD_PEEL_LEVELS) a child of odd size needs its own peel before the next step, so the pair cannot be one pass.
+// (In the other modes every extent is a multiple of 2^levels and this never vetoes.)
+inline bool fuse_here(Dims d, const char* sched)
+{
+    const Dims h = d.half();
+    return fuse_two_bfs(sched) && !((h.m | h.n | h.k) & 1);
+}
+
 // Bytes of workspace the executor takes for a problem of shape d (every extent a multiple of 2^levels) whose
 // remaining step order is `sched`, entered with `live` parents.  With T (m/2 x k/2), S (k/2 x n/2) and
 // Q (m/2 x n/2) the operands and the product of one child:  BFS step: T, S, Q for all seven children of
@@ -62,7 +71,7 @@ inline int64_t ws_need_bytes(Dims d, const char* sched, int64_t live, uint32_t r
     const Dims h = d.half();
     const int64_t W = (int64_t)sizeof(double);
     const int64_t eT = ws_mat_elems(h.m, h.k) * W, eS = ws_mat_elems(h.k, h.n) * W, eQ = ws_mat_elems(h.m, h.n) * W;
-    if (fuse_two_bfs(sched)) {
+    if (fuse_here(d, sched)) {
         const Dims q = h.half();
         const int64_t e4 = (ws_mat_elems(q.m, q.k) + ws_mat_elems(q.k, q.n) + ws_mat_elems(q.m, q.n)) * W;
         const int copies = (dbl && sched[2] == '\0') ? 2 : 1;

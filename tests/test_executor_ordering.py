@@ -265,6 +265,10 @@ def test_ring_wrap_and_the_fallback_are_reached():
     ((1001, 1001, 1001), 3, sw.SW_ODD_PEEL),        # peeled rows and columns
     ((94097, 94097, 94097), 5, sw.SW_ODD_PEEL),
     ((1001, 777, 1300), 2, sw.SW_ODD_PEEL),
+    ((1001, 1001, 1001), 3, sw.SW_ODD_PEEL_LEVELS),   # peeled at every odd level
+    ((94097, 94097, 94097), 5, sw.SW_ODD_PEEL_LEVELS),
+    ((255, 255, 255), 4, sw.SW_ODD_PEEL_LEVELS),      # odd at every level
+    ((1001, 777, 1300), 2, sw.SW_ODD_PEEL_LEVELS),
 ])
 def test_other_shapes_padding_and_peeling(shape, levels, odd):
     M, N, K = shape

@@ -220,6 +220,17 @@ def test_peeled_size_near_configuration_5(oracle):
         sw.sw_set_odd_mode(sw.SW_ODD_PAD)
 
 
+def test_peeled_at_every_level_near_configuration_5(oracle):
+    # the same size with peeling level by level: 94097 and 5881 are the odd levels (94097 -> 47048 -> 23524 -> 11762 -> 5881 -> 2940)
+    cfg = dict(inputs.CONFIGS[4], n=94097)
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
+    try:
+        s, worst, diff = _check_product(oracle, cfg, "integer", None)
+        assert s == "DDDBB"
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
 def test_configuration_5_integer(oracle):
     """The largest configuration on integer-valued inputs: sampled entries and Freivalds vectors exact, and 17 whole rows
     and 17 whole columns (border, top seams, leaf seams, tile edges) EQUAL to the oracle's strips of the definition."""

@@ -243,6 +243,62 @@ def test_peeling_matches_oracle(oracle, n, levels, schedules):
         sw.sw_set_odd_mode(sw.SW_ODD_PAD)
 
 
+@pytest.mark.parametrize("n,levels", [(3, 1), (97, 4), (127, 6), (263, 3), (777, 2), (1001, 3), (1000, 3), (2941, 2), (1470, 4)])
+def test_peeling_at_every_odd_level_matches_oracle(oracle, n, levels):
+    """SW_ODD_PEEL_LEVELS against the oracle's recursion with the same peeling (sizes odd at one, several or all
+    levels, and even ones): within the tolerance on real inputs, the exact product on integer-valued ones, the same
+    bits for every step order, no workspace beyond what the halved (rounded-down) extents need, and rows beyond n
+    of a wider C untouched."""
+    A = inputs.matrix(n, 7000 + n, 0, "uniform")
+    B = inputs.matrix(n, 7000 + n, 1, "rowscaled")
+    Ai = inputs.matrix(n, 8000 + n, 0, "integer")
+    Bi = inputs.matrix(n, 8000 + n, 1, "integer")
+    ref = oracle.gemm_peel(A, B, levels)
+    exact = (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64)
+    orders = ["".join("B" if (mask >> i) & 1 else "D" for i in range(levels)) for mask in range(1 << levels)]
+    if len(orders) > 8:
+        orders = orders[:2] + orders[len(orders) // 2 - 1:len(orders) // 2 + 2] + orders[-3:]
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
+    try:
+        assert sw.sw_plan_memory(n, levels, "D" * levels) <= sw.sw_plan_memory(n + 2 ** levels, levels, "D" * levels)
+        first = None
+        for s in orders:
+            got = run(A, B, levels, s)
+            assert float(np.max(np.abs(got - ref))) <= tol(n, A, B), s
+            if first is None:
+                first = got
+            assert np.array_equal(got, first), s
+            assert np.array_equal(run(Ai, Bi, levels, s), exact), s
+        # views with leading dimensions: nothing is written beside the n columns
+        ld = n + 5
+        big = [torch.zeros((n, ld), dtype=torch.float64, device=DEV) for _ in range(2)]
+        big[0][:, :n] = torch.from_numpy(Ai).to(DEV)
+        big[1][:, :n] = torch.from_numpy(Bi).to(DEV)
+        Cb = torch.full((n, ld), -7.0, dtype=torch.float64, device=DEV)
+        ws = torch.empty(max(256, sw.sw_plan_memory(n, levels, orders[-1])), dtype=torch.uint8, device=DEV)
+        sw.sw_gemm_ex(n, big[0], ld, big[1], ld, Cb, ld, levels, orders[-1], ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(Cb[:, :n].cpu().numpy(), exact) and bool((Cb[:, n:] == -7.0).all())
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
+def test_peeling_at_every_odd_level_on_rectangular_products():
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
+    try:
+        for (M, N, K, levels, order) in [(301, 515, 777, 3, "DBD"), (1001, 64, 333, 2, "BB"), (97, 97, 1030, 4, "DDBB"), (640, 641, 642, 3, "BDB")]:
+            g = torch.Generator(device=DEV).manual_seed(M + N)
+            A = torch.randint(-8, 9, (M, K), generator=g, device=DEV, dtype=torch.int32).to(torch.float64)
+            B = torch.randint(-8, 9, (K, N), generator=g, device=DEV, dtype=torch.int32).to(torch.float64)
+            C = torch.full((M, N), float("nan"), dtype=torch.float64, device=DEV)
+            ws = torch.empty(max(256, sw.sw_plan_memory_rect(M, N, K, levels, order)), dtype=torch.uint8, device=DEV)
+            sw.sw_gemm_rect(M, N, K, A, K, B, N, C, N, levels, order, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(C, A @ B), (M, N, K, order)
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
 @pytest.mark.parametrize("n,levels,sched", [(512, 2, "DD"), (1000, 3, "DBD"), (1200, 4, "DDBB"), (96, 5, "BDBDB"), (777, 2, "DB")])
 def test_dfs_steps_with_bfs_storage_give_the_same_bits(oracle, n, levels, sched):
     # with workspace beyond the minimum, DFS steps keep T, S, Q and use the one-pass addition kernels

@@ -97,6 +97,27 @@ def test_planner_prefers_bfs_and_puts_dfs_first():
             assert "BD" not in s            # DFS steps first (Limited-Memory shape)
 
 
+def test_plan_memory_with_peeling_at_every_level():
+    def elems(h):
+        ld = (h + 15) // 16 * 16
+        if ld >= 256 and ld % 256 == 0:
+            ld += 16
+        return (ld * h + 31) // 32 * 32
+    sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
+    try:
+        # extents halve rounding down: 1001 -> 500 -> 250 -> 125; no copies, nothing for the peeled parts
+        assert sw.sw_plan_memory(1001, 3, "DDD") == (2 * elems(500) + 2 * elems(250) + 2 * elems(125)) * 8
+        # a pair of BFS steps is one pass only where the level between them is even: 1001 -> 500 (even) fuses ...
+        assert sw.sw_plan_memory(1001, 2, "BB") == 3 * 49 * elems(250) * 8
+        # ... 1003 -> 501 (odd) does not: seven children of 501, then their 49 of 250
+        assert sw.sw_plan_memory(1003, 2, "BB") == (21 * elems(501) + 21 * 7 * elems(250)) * 8
+        assert sw.sw_plan_schedule(94097, 5, (290 << 30) - 3 * 94097 ** 2 * 8) == "DDDBB"
+        with pytest.raises(sw.SwError):
+            sw.sw_plan_memory(7, 3, "DDD")
+    finally:
+        sw.sw_set_odd_mode(sw.SW_ODD_PAD)
+
+
 def test_planner_picks_on_the_measured_sizes():
     """The planner's choice at the sizes where every step order was timed on the MI355X (profiles/step_orders.md):
     each pick below is the fastest measured order or within 0.3 % of it.  Only Limited-Memory shapes (DFS steps,
