@@ -233,6 +233,8 @@ def main():
     if args.kernel == "depth":
         return depth_study([int(x) for x in args.sizes.split(",")], args.max_levels)
     if args.kernel == "orders":
+        if args.levels < 1:
+            sys.exit("kernel_bench orders: give --levels (1 or more)")
         return order_study(args.n, args.levels, args.dist, args.seed)
     if args.kernel == "error_growth":
         return error_growth(args.n)
