@@ -170,57 +170,57 @@ struct Cols { int q, n0; int8_t c[MAXB][MAXQ]; };     // the blocks as combinati
     const int64_t r = t / hv, cc = (t - r * hv) * VEC
 
 // children[rows.n * p + i] = sum_k rows.c[i][k] * block k of parent p   (h x h each; block k = (k / n0, k % n0))
-template <int VEC>
+// (the block count per side N0 is a template parameter so that every loop over blocks unrolls)
+template <int VEC, int N0>
 __global__ __launch_bounds__(NT) void bil_pre_kernel(const double* parent, int64_t pld, int64_t pstride, int64_t h,
                                                      double* child, int64_t cld, int64_t cstride, Rows rows, int64_t bpm,
                                                      int64_t nblocks)
 {
     using P = Pack<VEC>;
-    const int nb = rows.n0 * rows.n0;
+    constexpr int NB = N0 * N0;
     for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
         BIL_DECODE();
         const double* src = parent + p * pstride + r * pld + cc;
-        P x[MAXB];
+        P x[NB];
 #pragma unroll
-        for (int k = 0; k < MAXB; ++k) {
-            if (k >= nb) continue;
+        for (int k = 0; k < NB; ++k) {
             bool used = false;
             for (int i = 0; i < rows.n; ++i) used = used || rows.c[i][k] != 0;
-            if (used) x[k] = P::ld(src + (k / rows.n0) * h * pld + (k % rows.n0) * h);
+            if (used) x[k] = P::ld(src + (k / N0) * h * pld + (k % N0) * h);
         }
         for (int i = 0; i < rows.n; ++i) {
             P acc{};
             bool started = false;
 #pragma unroll
-            for (int k = 0; k < MAXB; ++k)
-                if (k < nb) term(acc, started, rows.c[i][k], x[k]);
+            for (int k = 0; k < NB; ++k) term(acc, started, rows.c[i][k], x[k]);
             acc.st(child + (p * rows.n + i) * cstride + r * cld + cc);
         }
     }
 }
 
 // block c of parent p = sum_i cols.c[c][i] * prod[cols.q * p + i]
-template <int VEC>
+template <int VEC, int N0>
 __global__ __launch_bounds__(NT) void bil_post_kernel(const double* prod, int64_t qld, int64_t qstride, int64_t h,
                                                       double* parent, int64_t pld, int64_t pstride, Cols cols, int64_t bpm,
                                                       int64_t nblocks)
 {
     using P = Pack<VEC>;
-    const int nb = cols.n0 * cols.n0;
+    constexpr int NB = N0 * N0, QMAX = N0 * N0 * N0;      // no scheme has more products than the classical one
     for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
         BIL_DECODE();
-        P x[MAXQ];
+        P x[QMAX];
 #pragma unroll
-        for (int i = 0; i < MAXQ; ++i)
+        for (int i = 0; i < QMAX; ++i)
             if (i < cols.q) x[i] = P::ld(prod + (p * cols.q + i) * qstride + r * qld + cc);
         double* dst = parent + p * pstride + r * pld + cc;
-        for (int c = 0; c < nb; ++c) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
             P acc{};
             bool started = false;
 #pragma unroll
-            for (int i = 0; i < MAXQ; ++i)
+            for (int i = 0; i < QMAX; ++i)
                 if (i < cols.q) term(acc, started, cols.c[c][i], x[i]);
-            acc.st(dst + (c / cols.n0) * h * pld + (c % cols.n0) * h);
+            acc.st(dst + (c / N0) * h * pld + (c % N0) * h);
         }
     }
 }
@@ -229,20 +229,21 @@ __global__ __launch_bounds__(NT) void bil_post_kernel(const double* prod, int64_
 // C_c = w[c] * Q when it is the block's first product, else C_c = C_c + w[c] * Q.
 struct Fold { int n0; int8_t w[MAXB]; int8_t first[MAXB]; };
 
-template <int VEC>
+template <int VEC, int N0>
 __global__ __launch_bounds__(NT) void bil_fold_kernel(const double* prod, int64_t qld, int64_t qstride, int64_t h,
                                                       double* parent, int64_t pld, int64_t pstride, Fold f, int64_t bpm,
                                                       int64_t nblocks)
 {
     using P = Pack<VEC>;
-    const int nb = f.n0 * f.n0;
+    constexpr int NB = N0 * N0;
     for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
         BIL_DECODE();
         const P x = P::ld(prod + p * qstride + r * qld + cc);
         double* dst = parent + p * pstride + r * pld + cc;
-        for (int c = 0; c < nb; ++c) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
             if (f.w[c] == 0) continue;
-            double* d = dst + (c / f.n0) * h * pld + (c % f.n0) * h;
+            double* d = dst + (c / N0) * h * pld + (c % N0) * h;
             P acc{};
             bool started = false;
             if (!f.first[c]) { acc = P::ld(d); started = true; }
@@ -270,9 +271,13 @@ hipError_t launch_pre(Mat parent, int64_t live, int64_t h, Mat child, const Rows
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = h % 2 == 0 && vec2(parent) && vec2(child);
     const Grid g = grid_for(live, h, v2 ? 2 : 1);
-    if (v2) hipLaunchKernelGGL((bil_pre_kernel<2>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
+    if (v2 && rows.n0 == 2)      hipLaunchKernelGGL((bil_pre_kernel<2, 2>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
                                child.p, child.ld, child.stride, rows, g.bpm, g.nblocks);
-    else    hipLaunchKernelGGL((bil_pre_kernel<1>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
+    else if (v2)                hipLaunchKernelGGL((bil_pre_kernel<2, 3>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
+                               child.p, child.ld, child.stride, rows, g.bpm, g.nblocks);
+    else if (rows.n0 == 2)     hipLaunchKernelGGL((bil_pre_kernel<1, 2>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
+                               child.p, child.ld, child.stride, rows, g.bpm, g.nblocks);
+    else                        hipLaunchKernelGGL((bil_pre_kernel<1, 3>), dim3(g.blocks), dim3(NT), 0, s, parent.p, parent.ld, parent.stride, h,
                                child.p, child.ld, child.stride, rows, g.bpm, g.nblocks);
     return hipGetLastError();
 }
@@ -282,9 +287,13 @@ hipError_t launch_post(Mat prod, int64_t live, int64_t h, Mat parent, const Cols
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = h % 2 == 0 && vec2(parent) && vec2(prod);
     const Grid g = grid_for(live, h, v2 ? 2 : 1);
-    if (v2) hipLaunchKernelGGL((bil_post_kernel<2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+    if (v2 && cols.n0 == 2)      hipLaunchKernelGGL((bil_post_kernel<2, 2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
                                parent.p, parent.ld, parent.stride, cols, g.bpm, g.nblocks);
-    else    hipLaunchKernelGGL((bil_post_kernel<1>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+    else if (v2)                hipLaunchKernelGGL((bil_post_kernel<2, 3>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+                               parent.p, parent.ld, parent.stride, cols, g.bpm, g.nblocks);
+    else if (cols.n0 == 2)     hipLaunchKernelGGL((bil_post_kernel<1, 2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+                               parent.p, parent.ld, parent.stride, cols, g.bpm, g.nblocks);
+    else                        hipLaunchKernelGGL((bil_post_kernel<1, 3>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
                                parent.p, parent.ld, parent.stride, cols, g.bpm, g.nblocks);
     return hipGetLastError();
 }
@@ -294,9 +303,13 @@ hipError_t launch_fold(Mat prod, int64_t live, int64_t h, Mat parent, const Fold
     if (live == 0 || h == 0) return hipSuccess;
     const bool v2 = h % 2 == 0 && vec2(parent) && vec2(prod);
     const Grid g = grid_for(live, h, v2 ? 2 : 1);
-    if (v2) hipLaunchKernelGGL((bil_fold_kernel<2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+    if (v2 && f.n0 == 2)      hipLaunchKernelGGL((bil_fold_kernel<2, 2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
                                parent.p, parent.ld, parent.stride, f, g.bpm, g.nblocks);
-    else    hipLaunchKernelGGL((bil_fold_kernel<1>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+    else if (v2)                hipLaunchKernelGGL((bil_fold_kernel<2, 3>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+                               parent.p, parent.ld, parent.stride, f, g.bpm, g.nblocks);
+    else if (f.n0 == 2)     hipLaunchKernelGGL((bil_fold_kernel<1, 2>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
+                               parent.p, parent.ld, parent.stride, f, g.bpm, g.nblocks);
+    else                        hipLaunchKernelGGL((bil_fold_kernel<1, 3>), dim3(g.blocks), dim3(NT), 0, s, prod.p, prod.ld, prod.stride, h,
                                parent.p, parent.ld, parent.stride, f, g.bpm, g.nblocks);
     return hipGetLastError();
 }
