@@ -20,9 +20,12 @@
 //     contiguous run of tiles, ordered in groups of 8 tile rows: the ~64 tiles in flight on an XCD then
 //     share A row panels and B column panels through that L2;
 //   * edges: rows and columns beyond m are clamped to the last valid one on load (their products land in
-//     accumulators that are never stored); the K tail is zero-filled; stores are bounds-checked.  16-byte
-//     global loads when pointers and leading dimensions allow it (an odd m too, if rows are padded),
-//     8-byte loads otherwise.
+//     accumulators that are never stored); the K tail is zero-filled; stores are bounds-checked on tiles that
+//     reach beyond the matrix and unchecked (one address update per four rows) on tiles inside it.  A cell of the
+//     128 x 128 grid that holds at most 64 or 96 rows (columns) of the matrix runs a body with 2 or 3 MFMA tiles
+//     per wavefront in that direction instead of 4, so an edge cell issues only the MFMAs its part of the
+//     matrix needs (to the next multiple of 32).  16-byte global loads when pointers and leading dimensions
+//     allow it (an odd m too, if rows are padded), 8-byte loads otherwise.
 #include <type_traits>
 
 #include "sw_internal.h"
