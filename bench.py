@@ -163,17 +163,52 @@ def main():
         else:
             sw.sw_gemm_bilinear_levels(n, A, B, C, schedule, per_level)
 
-    for _ in range(args.warmup):
-        step()
+    def run_steps(count, what):
+        """Enqueue `count` products back to back (no host synchronisation between the launches) and report each one on
+        stderr when the GPU has finished it: an event per product on the launch stream, waited for by a reporter thread
+        (the enqueueing thread itself is held back by the depth of the HIP queues and gets to the events late)."""
+        import queue
+        import threading
+        done = queue.Queue()
+
+        def report():
+            k = 0
+            while True:
+                ev = done.get()
+                if ev is None:
+                    return
+                ev.synchronize()
+                k += 1
+                print(f"bench.py: {what} product {k} of {count} done", file=sys.stderr, flush=True)
+
+        t = threading.Thread(target=report, daemon=True)
+        t.start()
+        for _ in range(count):
+            step()
+            ev = torch.cuda.Event()
+            ev.record()
+            done.put(ev)
+        done.put(None)
+        torch.cuda.synchronize()
+        t.join()
+
+    run_steps(args.warmup, "warm-up")
     torch.cuda.synchronize()
     sw.sw_profile_enable(True)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
+    run_steps(args.steps, "timed")
     dt = time.perf_counter() - t0
     prof = sw.sw_profile_read()
     sw.sw_profile_enable(False)
+
+    # The timed steps carry two HIP events around every kernel (that is where the roofline's launch durations come
+    # from).  One more product without them, outside the timed region, shows what the brackets cost.
+    plain_ms = None
+    if not args.no_reference:
+        t2 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        plain_ms = (time.perf_counter() - t2) * 1e3
 
     # The timed steps run with the library's default executor (three streams: additions beside the leaf
     # products), where the leaf kernel shares the machine with the addition kernels and its launches stretch.
@@ -265,6 +300,10 @@ def main():
                       "note": ("kernel time summed over streams: the leaf-side addition kernels run capped at 32 workgroups "
                                "beside the products, so their own rate is low by design; `single_stream` has them alone" if alone else None)},
         "leaf_ms_per_step": round(leaf["ms"] / args.steps, 3),
+        "event_brackets": {"in_timed_region": True, "kernels_per_step": sum(p["launches"] for p in prof.values()) // max(1, args.steps),
+                           "one_product_without_them_ms": None if plain_ms is None else round(plain_ms, 3),
+                           "note": "every kernel of the timed steps is bracketed by two HIP events on its launch stream (the source of "
+                                   "roofline.avg_launch_ms); one more product without the brackets is timed after the timed region"},
         "single_stream": alone,
         "check": {"freivalds_max_abs_diff": check, "tolerance": tol, "ok": check <= tol},
         "paper_context": "Cray XT4: 49.1 effective GFLOPS/node, 33% above the classical peak (Section 5.2)",
