@@ -136,28 +136,30 @@ def stream_sweep(total_bytes, iters):
     import os
     import torch
     L = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsw_probe.so"))
-    L.sw_probe_streams.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
-                                   ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    L.sw_probe_streams.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                   ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
     dev = "cuda:0"
     torch.cuda.set_device(0)
     st = torch.cuda.current_stream().cuda_stream
-    print("| streams in | streams out | GB per launch | ms | TB/s | of 8 TB/s |")
-    print("|---|---|---|---|---|---|")
-    for nin, nout in [(0, 1), (1, 0), (1, 1), (2, 1), (4, 1), (1, 4), (1, 8), (4, 4), (8, 8), (16, 16), (5, 3), (4, 7), (7, 4), (16, 49), (49, 16)]:
+    print("| streams in | streams out | pieces per workgroup and stream | GB per launch | ms | TB/s | of 8 TB/s |")
+    print("|---|---|---|---|---|---|---|")
+    shapes = [(0, 1), (1, 0), (1, 1), (2, 1), (4, 1), (1, 4), (1, 8), (4, 4), (8, 8), (16, 16), (5, 3), (4, 7), (7, 4), (16, 49), (49, 16)]
+    cases = [(i, o, 1) for i, o in shapes] + [(i, o, 4) for i, o in [(1, 8), (4, 7), (7, 4), (16, 49)]]
+    for nin, nout, chunks in cases:
         n2 = total_bytes // (nin + nout) // 16
         n2 -= n2 % 4096
         stride = n2 + 4096 + 16            # streams a little more than their length apart, never a power of two
         a = torch.rand(max(nin, 1) * stride * 2, dtype=torch.float64, device=dev)
         o = torch.empty(max(nout, 1) * stride * 2, dtype=torch.float64, device=dev)
-        blocks = min((n2 + 255) // 256, 1 << 20)
+        blocks = min((n2 + 256 * chunks - 1) // (256 * chunks), 1 << 20)
 
         def launch():
-            rc = L.sw_probe_streams(nin, nout, a.data_ptr(), o.data_ptr(), n2, stride, stride, blocks, st)
+            rc = L.sw_probe_streams(nin, nout, chunks, a.data_ptr(), o.data_ptr(), n2, stride, stride, blocks, st)
             assert rc == 0, rc
         ms = _timed(launch, iters, 2)
         moved = (nin + nout) * n2 * 16
         rate = moved / (ms * 1e-3) / 1e12
-        print(f"| {nin} | {nout} | {moved / 1e9:.2f} | {ms:.3f} | {rate:.2f} | {100 * rate / 8.0:.0f} % |", flush=True)
+        print(f"| {nin} | {nout} | {chunks} | {moved / 1e9:.2f} | {ms:.3f} | {rate:.2f} | {100 * rate / 8.0:.0f} % |", flush=True)
         del a, o
         torch.cuda.empty_cache()
 
