@@ -3,7 +3,8 @@
 // access, one pass, non-temporal hints -- the access pattern of the addition kernels without their arithmetic
 // detail.  kernel_bench's `streams` command sweeps (NIN, NOUT) to show how the rate HBM sustains depends on the
 // number of streams a kernel reads and writes at once; that sweep is the ceiling the addition kernels are
-// measured against.
+// measured against.  Its `beside` command runs the leaf products next to background traffic of a chosen number of
+// workgroups (load_kernel) and reads the shader clock meanwhile (meter_kernel).
 #include <stdint.h>
 
 #include <hip/hip_runtime.h>
@@ -49,6 +50,40 @@ __global__ void __launch_bounds__(256) streams_kernel(const v2d* __restrict__ in
     }
 }
 
+// Background traffic for the `beside` measurement: `reps` passes over n2 elements of 16 bytes with however many
+// workgroups it is launched with.  mode 0: copy (one stream in, one out), 1: read only, 2: write only.
+__global__ void __launch_bounds__(256) load_kernel(const v2d* __restrict__ in, v2d* __restrict__ out, int64_t n2, int reps, int mode,
+                                                   int guard)
+{
+    v2d keep = (v2d){0.0, 0.0};
+    for (int r = 0; r < reps; ++r) {
+        for (int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x; i + 768 < n2; i += (int64_t)gridDim.x * 1024) {
+            v2d x[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[c] = mode == 2 ? (v2d){1.0 + r, 2.0} : __builtin_nontemporal_load(in + i + c * 256);
+            if (mode == 1) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) keep += x[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) __builtin_nontemporal_store(x[c], out + i + c * 256);
+            }
+        }
+    }
+    if (mode == 1 && guard && keep[0] == 0.12345) out[threadIdx.x] = keep;
+}
+
+// One wavefront that sleeps `iters` times about 8000 clocks and notes the shader-clock counter and the constant
+// 100 MHz counter before and after: out[0..3] = clock at start, at end, 100 MHz count at start, at end.  Their
+// ratio is the average shader clock while other kernels run.
+__global__ void __launch_bounds__(64) meter_kernel(int64_t* out, int iters)
+{
+    const int64_t c0 = clock64(), w0 = wall_clock64();
+    for (int i = 0; i < iters; ++i) __builtin_amdgcn_s_sleep(127);
+    const int64_t c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0) { out[0] = c0; out[1] = c1; out[2] = w0; out[3] = w1; }
+}
+
 }  // namespace
 
 // n2: elements of 16 bytes per stream; chunks: 1, or 4 for (1, 8), (4, 7), (7, 4) and (16, 49) streams;
@@ -71,4 +106,21 @@ extern "C" int sw_probe_streams(int nin, int nout, int chunks, const void* in, v
     SW_CASE(1, 8, 4) SW_CASE(4, 7, 4) SW_CASE(7, 4, 4) SW_CASE(16, 49, 4)
 #undef SW_CASE
     return -1;
+}
+
+// Background traffic (see load_kernel): in / out hold n2 elements of 16 bytes each (n2 >= 1024).  Returns 0, -1 for
+// arguments out of range, or the HIP error code.
+extern "C" int sw_probe_load(const void* in, void* out, int64_t n2, int reps, int mode, int blocks, void* hip_stream)
+{
+    if (blocks < 1 || n2 < 1024 || reps < 0 || mode < 0 || mode > 2) return -1;
+    hipLaunchKernelGGL(load_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, (const v2d*)in, (v2d*)out, n2, reps, mode, 0);
+    return (int)hipGetLastError();
+}
+
+// The clock meter (see meter_kernel): out holds four int64.
+extern "C" int sw_probe_meter(void* out, int iters, void* hip_stream)
+{
+    if (iters < 0) return -1;
+    hipLaunchKernelGGL(meter_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (int64_t*)out, iters);
+    return (int)hipGetLastError();
 }

@@ -15,6 +15,8 @@
                                                                             # that fits, next to the planner's pick
   python -m paper_1202_3173_amd.kernel_bench streams --bytes 8589934592       # synthetic kernels with r input and w
                                                                             # output streams: what HBM sustains
+  python -m paper_1202_3173_amd.kernel_bench beside --m 2940 --batch 49       # leaf products next to background
+                                                                            # traffic, with the shader clock
   python -m paper_1202_3173_amd.kernel_bench error_growth --n 2048           # error against the depth, with and
                                                                             # without diagonal scaling (Section 6.1)
 
@@ -164,6 +166,76 @@ def stream_sweep(total_bytes, iters):
         torch.cuda.empty_cache()
 
 
+def beside_study(m, batch, launches):
+    """The leaf products next to background traffic: `launches` launches of `batch` products of m^3 on one stream while a
+    streaming kernel of a chosen number of workgroups runs on another and a one-wavefront meter reads the shader
+    clock on a third.  Markdown table: background, its rate, the median launch, its rate, the average shader clock."""
+    import ctypes
+    import os
+    import time
+    import torch
+    from . import binding as sw
+    X = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsw_probe.so"))
+    X.sw_probe_load.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    X.sw_probe_meter.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    s_gemm, s_load, s_meter = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    n2 = (2 << 30) // 16
+    src = torch.rand(n2 * 2, dtype=torch.float64, device=dev)
+    dst = torch.empty(n2 * 2, dtype=torch.float64, device=dev)
+    stamps = torch.zeros(4, dtype=torch.int64, device=dev)
+    ld = (m + 15) // 16 * 16
+    if ld >= 256 and ld % 256 == 0:
+        ld += 16
+    stride = (ld * m + 31) // 32 * 32
+    A = torch.rand(batch * stride, dtype=torch.float64, device=dev) - 0.5
+    B = torch.rand(batch * stride, dtype=torch.float64, device=dev) - 0.5
+    C = torch.empty(batch * stride, dtype=torch.float64, device=dev)
+    flops = 2.0 * m ** 3 * batch
+    print(f"| background beside {batch} products of {m}^3 | its rate while the products run, TB/s | median launch ms | TFLOP/s | of the fp64 MFMA peak | shader clock MHz |")
+    print("|---|---|---|---|---|---|")
+    for label, mode, blocks in [("none", 0, 0), ("copy, 32 workgroups", 0, 32), ("copy, 96 workgroups", 0, 96), ("copy, 256 workgroups", 0, 256),
+                                ("read only, 96 workgroups", 1, 96), ("write only, 96 workgroups", 2, 96), ("none", 0, 0)]:
+        torch.cuda.synchronize()
+        # the meter runs for about three quarters of the time the launches take (about 3.5 us per iteration), so it
+        # ends while they still run; the background traffic is cut into pieces of a few milliseconds, timed one by one,
+        # enough of them to outlast the products
+        est_ms = launches * flops / 50e12 * 1e3
+        assert X.sw_probe_meter(stamps.data_ptr(), int(0.75 * launches * flops / 75e12 * 1e6 / 3.5), s_meter.cuda_stream) == 0
+        pieces = []
+        if blocks:
+            reps = max(1, blocks // 32)
+            for _ in range(int(est_ms / 2.0) + 8):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(s_load)
+                assert X.sw_probe_load(src.data_ptr(), dst.data_ptr(), n2, reps, mode, blocks, s_load.cuda_stream) == 0
+                e1.record(s_load)
+                pieces.append((e0, e1))
+            time.sleep(0.01)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+        ev[0].record(s_gemm)
+        for i in range(launches):
+            with torch.cuda.stream(s_gemm):
+                sw.sw_leaf_gemm(m, batch, A, ld, stride, B, ld, stride, C, ld, stride)
+            ev[i + 1].record(s_gemm)
+        torch.cuda.synchronize()
+        t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(1, launches))
+        mid = t[len(t) // 2]
+        st = stamps.cpu().tolist()
+        mhz = (st[1] - st[0]) / ((st[3] - st[2]) / 100.0)
+        rate = "-"
+        if blocks:
+            # pieces that ran wholly while the products ran: those that began after the first launch ended and ended
+            # before the last launch did
+            inside = [p for p in pieces if ev[1].elapsed_time(p[0]) > 0 and p[1].elapsed_time(ev[launches]) > 0]
+            if inside:
+                span = inside[0][0].elapsed_time(inside[-1][1])
+                moved = len(inside) * reps * n2 * 16 * (2 if mode == 0 else 1)
+                rate = f"{moved / span / 1e9:.2f}"
+        print(f"| {label} | {rate} | {mid:.3f} | {flops / mid / 1e9:.1f} | {flops / mid / 1e9 / FP64_MFMA_PEAK_TFLOPS:.3f} | {mhz:.0f} |", flush=True)
+
+
 def error_growth(n):
     """Markdown tables: the largest entry-wise error relative to ||A(i,:)|| ||B(:,j)|| (the quantity the scaled bound
     of Section 6.1 is stated in) in units of n*eps, and in brackets the norm-wise error in units of
@@ -209,7 +281,7 @@ def error_growth(n):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "pre_add2", "post_add2", "copy", "dgemm", "depth", "orders", "streams", "error_growth"])
+    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "pre_add2", "post_add2", "copy", "dgemm", "depth", "orders", "streams", "beside", "error_growth"])
     ap.add_argument("--sizes", default="2048,4096,8192,16384,23520,32768,47040", help="depth: the sizes n")
     ap.add_argument("--max-levels", type=int, default=6, help="depth: the largest depth tried")
     ap.add_argument("--n", type=int, default=2048, help="orders, error_growth: the size n")
@@ -242,6 +314,8 @@ def main():
         return error_growth(args.n)
     if args.kernel == "streams":
         return stream_sweep(args.bytes, args.iters)
+    if args.kernel == "beside":
+        return beside_study(args.m, args.batch, args.iters)
 
     import torch
     from paper_1202_3173_amd import binding as sw
