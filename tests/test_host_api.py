@@ -36,7 +36,7 @@ def test_model_words_closed_forms():
     n, l, k = 94080, 3, 2
     lm = sum(3 * n * n // 4 ** i for i in range(l)) + (7 * (n >> l) ** 2 * 7 ** k // 4 ** k - 4 * (n >> l) ** 2)
     assert sw.sw_model_words(n, l + k, "DDDBB") == lm
-    # the survey's table of the paper-model footprint at n = 94080 (GB, incl. A, B, C)
+    # the paper-model footprint at n = 94080 worked out by hand from the two formulas above (GB, incl. A, B, C)
     for sched, gb in [("DDDDD", 283.16), ("DDDDB", 284.41), ("DDDBD", 289.39), ("DDDBB", 298.10)]:
         assert sw.sw_model_words(94080, 5, sched) * 8 / 1e9 == pytest.approx(gb, abs=0.01)
 
