@@ -22,7 +22,7 @@ PROBE_LIB = os.path.join(HERE, "libsw_probe.so")
 COMMON = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wall", "-Wno-unused-command-line-argument"]
-PRODUCT_SOURCES = ["sw_api.hip", "sw_add_kernels.hip", "sw_leaf_gemm.hip", "sw_scale_kernels.hip", "sw_bilinear.hip", "sw_dgemm.hip", "sw_static.hip"]
+PRODUCT_SOURCES = ["sw_api.hip", "sw_add_kernels.hip", "sw_leaf_gemm.hip", "sw_scale_kernels.hip", "sw_bilinear.hip", "sw_dgemm.hip", "sw_static.hip", "sw_peel_kernels.hip"]
 
 
 def _run(cmd):

@@ -417,6 +417,31 @@ pad_copy_kernel(const double* __restrict__ src, int64_t sld, int rows, int cols,
     }
 }
 
+// ---- dense copies of thin strips ------------------------------------------------------------------------------------
+// dst_b (rows x cols, pitch dld) = src_b (pitch sld) for every matrix b of the batch: the peeled column of an A and the
+// peeled row of a B are set aside with it, so that the operands themselves are free again before the update that
+// uses the strips runs.
+__global__ void __launch_bounds__(NT)
+strip_copy_kernel(const double* __restrict__ src, int64_t sld, int64_t sstride, int rows, int cols, double* __restrict__ dst,
+                  int64_t dld, int64_t dstride, LGrid lg)
+{
+    SW_LOGICAL_BLOCKS(lg) {
+        SW_DECODE_BLOCK(lg)
+        [=]() {
+            const int c = bx * NT + threadIdx.x;
+            if (c >= cols) return;
+            const int r0 = by * PAD_ROWS;
+            const double* S = src + (int64_t)bz * sstride;
+            double* D = dst + (int64_t)bz * dstride;
+        #pragma unroll
+            for (int r = 0; r < PAD_ROWS; ++r) {
+                const int row = r0 + r;
+                if (row < rows) D[(int64_t)row * dld + c] = S[(int64_t)row * sld + c];
+            }
+        }();
+    }
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool even(int64_t v) { return (v & 1) == 0; }
 inline bool mat_vec2(const Mat& m) { return aligned16(m.p) && even(m.ld) && even(m.stride); }
@@ -569,6 +594,16 @@ hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int6
     const LGrid lg{(unsigned)((pcols + NT - 1) / NT), (unsigned)((prows + PAD_ROWS - 1) / PAD_ROWS), 1u};
     hipLaunchKernelGGL(pad_copy_kernel, physical(lg), dim3(NT), 0, s, src, src_ld, (int)rows, (int)cols, dst, dst_ld,
                        (int)prows, (int)pcols, lg);
+    return hipGetLastError();
+}
+
+hipError_t launch_strip_copy(Mat src, int64_t rows, int64_t cols, Mat dst, int64_t live, hipStream_t s)
+{
+    if (live == 0 || rows == 0 || cols == 0) return hipSuccess;
+    if (Tracer* t = tracer()) return t->kernel(Tracer::K_PAD_COPY, s, {fp(src, rows, cols, live)}, {fp(dst, rows, cols, live)});
+    const LGrid lg{(unsigned)((cols + NT - 1) / NT), (unsigned)((rows + PAD_ROWS - 1) / PAD_ROWS), (unsigned)live};
+    hipLaunchKernelGGL(strip_copy_kernel, physical(lg), dim3(NT), 0, s, src.p, src.ld, src.stride, (int)rows, (int)cols, dst.p, dst.ld,
+                       dst.stride, lg);
     return hipGetLastError();
 }
 

@@ -498,24 +498,47 @@ struct Exec {
             // Peeling at this level (Section 3.1, "dynamic peeling"): the step runs on the leading even extents, in
             // place; the last row, column and inner index of all `live` problems are finished by thin classical
             // products on the MFMA kernel.  Behind every row of the even part lies the peeled element.
+            //   before the step:  c12 = [A11 a12] * [b12; b22],  [c21 c22] = [a21 a22] * B,  copies of a12 and b21
+            //   after it:         C11 += a12 * b21  from the copies
+            // so that A and B are read for the last time before the step's own kernels: were the strips read from A
+            // and B after it, whatever forms the operands of the NEXT problem in the same buffers would have to wait
+            // for this problem's products, and the leaf products would stand still meanwhile.
             const Dims e{d.m & ~(int64_t)1, d.n & ~(int64_t)1, d.k & ~(int64_t)1};
             const int64_t rm = d.m - e.m, rn = d.n - e.n, rk = d.k - e.k;
             Mat Ae = A, Be = B, Ce = C;
             Ae.padded = A.padded || rk;
             Be.padded = B.padded || rn;
             Ce.padded = C.padded || rn;
-            mul(Ae, Be, Ce, e, level, live);                             // C11  = A11 * B11
+            const bool thin = thin_grid_ok(d.m > d.n ? d.m : d.n, live);   // the streaming one-wide kernels, else the MFMA kernel
+            const int64_t mark = used;
+            const int64_t sa = (e.m + 31) / 32 * 32, sb = (e.n + 31) / 32 * 32;
+            const Mat a12c{rk ? take(live * sa) : nullptr, 1, sa, false}, b21c{rk ? take(live * sb) : nullptr, e.n, sb, false};
             const Mat a12{A.p + e.k, A.ld, A.stride, A.padded}, b21{B.p + e.k * B.ld, B.ld, B.stride, B.padded};
             const Mat bright{B.p + e.n, B.ld, B.stride, B.padded}, c12{C.p + e.n, C.ld, C.stride, C.padded};
             const Mat abot{A.p + e.m * A.ld, A.ld, A.stride, A.padded}, cbot{C.p + e.m * C.ld, C.ld, C.stride, C.padded};
-            op(S_POST, SW_CLASS_PEEL,
-               2.0 * live * ((double)e.m * e.n * rk + (double)e.m * rn * d.k + (double)rm * d.n * d.k),
-               {rng(A, d.m, d.k, live), rng(B, d.k, d.n, live)}, {rng(C, d.m, d.n, live)}, [&](hipStream_t st) {
-                   hipError_t e1 = rk ? launch_gemm(e.m, e.n, rk, live, a12, b21, Ce, true, st) : hipSuccess;        // C11 += a12 * b21
-                   hipError_t e2 = rn ? launch_gemm(e.m, rn, d.k, live, A, bright, c12, false, st) : hipSuccess;     // c12  = [A11 a12] * [b12; b22]
-                   hipError_t e3 = rm ? launch_gemm(rm, d.n, d.k, live, abot, B, cbot, false, st) : hipSuccess;      // [c21 c22] = [a21 a22] * B
-                   return e1 != hipSuccess ? e1 : (e2 != hipSuccess ? e2 : e3);
-               });
+            if (rk && e.m && e.n)
+                op(S_POST, SW_CLASS_PEEL, 0.0, {rng(A, d.m, d.k, live), rng(B, d.k, d.n, live)},
+                   {rng(a12c, e.m, 1, live), rng(b21c, 1, e.n, live)}, [&](hipStream_t st) {
+                       hipError_t e1 = launch_strip_copy(a12, e.m, 1, a12c, live, st);
+                       hipError_t e2 = launch_strip_copy(b21, 1, e.n, b21c, live, st);
+                       return e1 != hipSuccess ? e1 : e2;
+                   });
+            if (rn || rm)
+                op(S_POST, SW_CLASS_PEEL, 2.0 * live * ((double)e.m * rn * d.k + (double)rm * d.n * d.k),
+                   {rng(A, d.m, d.k, live), rng(B, d.k, d.n, live)}, {rng(C, d.m, d.n, live)}, [&](hipStream_t st) {
+                       // c12 = [A11 a12] * [b12; b22] and [c21 c22] = [a21 a22] * B
+                       hipError_t e2 = !rn ? hipSuccess : (thin ? launch_matvec(e.m, d.k, live, A, bright, c12, st) : launch_gemm(e.m, rn, d.k, live, A, bright, c12, false, st));
+                       hipError_t e3 = !rm ? hipSuccess : (thin ? launch_vecmat(d.n, d.k, live, abot, B, cbot, st) : launch_gemm(rm, d.n, d.k, live, abot, B, cbot, false, st));
+                       return e2 != hipSuccess ? e2 : e3;
+                   });
+            mul(Ae, Be, Ce, e, level, live);                             // C11  = A11 * B11
+            if (rk && e.m && e.n)
+                op(S_POST, SW_CLASS_PEEL, 2.0 * live * (double)e.m * e.n * rk, {rng(a12c, e.m, 1, live), rng(b21c, 1, e.n, live), rng(C, d.m, d.n, live)},
+                   {rng(C, d.m, d.n, live)},
+                   [&](hipStream_t st) {                                                                  // C11 += a12 * b21
+                       return thin ? launch_rank1(e.m, e.n, live, a12c, b21c, Ce, st) : launch_gemm(e.m, e.n, rk, live, a12c, b21c, Ce, true, st);
+                   });
+            pop_to(mark);
             return;
         }
         const Dims h = d.half();

@@ -35,6 +35,15 @@ struct Dims {
 inline int64_t ws_mat_elems(int64_t rows, int64_t cols) { return (ws_ld(cols) * rows + 31) / 32 * 32; }
 inline int64_t ws_mat_elems(int64_t h) { return ws_mat_elems(h, h); }
 
+// Elements of the dense copies a problem with an odd inner extent sets aside when that index is peeled: the last
+// column of A over the even rows and the last row of B over the even columns, each rounded up to 32 doubles.
+inline int64_t peel_side_elems(Dims d)
+{
+    if (!(d.k & 1)) return 0;
+    const int64_t em = d.m & ~(int64_t)1, en = d.n & ~(int64_t)1;
+    return (em + 31) / 32 * 32 + (en + 31) / 32 * 32;
+}
+
 // A run of consecutive BFS steps is executed in fused pairs, deepest pairs first: with an even number of B
 // ahead the next two steps share one pass and the operands of the level between them are never stored.
 inline bool fuse_two_bfs(const char* sched)
@@ -68,6 +77,12 @@ inline bool fuse_here(Dims d, const char* sched)
 inline int64_t ws_need_bytes(Dims d, const char* sched, int64_t live, uint32_t rich = 0, bool dbl = false)
 {
     if (*sched == '\0') return 0;
+    if ((d.m | d.n | d.k) & 1) {
+        // an odd extent is peeled before the step (SW_ODD_PEEL_LEVELS; in the other modes no step sees one): the
+        // step runs on the even part, and a peeled inner index sets its column of A and row of B aside
+        const Dims e{d.m & ~(int64_t)1, d.n & ~(int64_t)1, d.k & ~(int64_t)1};
+        return live * peel_side_elems(d) * (int64_t)sizeof(double) + ws_need_bytes(e, sched, live, rich, dbl);
+    }
     const Dims h = d.half();
     const int64_t W = (int64_t)sizeof(double);
     const int64_t eT = ws_mat_elems(h.m, h.k) * W, eS = ws_mat_elems(h.k, h.n) * W, eQ = ws_mat_elems(h.m, h.n) * W;
@@ -264,6 +279,15 @@ inline hipError_t launch_dfs_post(Mat x, Mat c11, Mat c12, Mat c21, Mat c22, int
     return launch_dfs_post(x, c11, c12, c21, c22, live, h, h, s);
 }
 // Zero-padded copy / crop.
+// One-wide products of a peeled level, batched over `live` problems (a column x: element k at x.p + k * x.ld; a row:
+// contiguous).  y = A x (A: M x K);  y = x B (B: K x N);  C += u v (u a column of M, v a row of N).
+// thin_grid_ok: whether the three fit the launch limits (else the MFMA kernel does the same products).
+hipError_t launch_matvec(int64_t M, int64_t K, int64_t live, Mat a, Mat x, Mat y, hipStream_t s);
+hipError_t launch_vecmat(int64_t N, int64_t K, int64_t live, Mat x, Mat b, Mat y, hipStream_t s);
+hipError_t launch_rank1(int64_t M, int64_t N, int64_t live, Mat u, Mat v, Mat c, hipStream_t s);
+inline bool thin_grid_ok(int64_t M, int64_t live) { return live <= 65535 && (M + 3) / 4 <= 65535; }
+// dst_b = src_b (rows x cols) for b < live: dense copies of thin strips
+hipError_t launch_strip_copy(Mat src, int64_t rows, int64_t cols, Mat dst, int64_t live, hipStream_t s);
 hipError_t launch_pad_copy(const double* src, int64_t src_ld, int64_t rows, int64_t cols, double* dst,
                            int64_t dst_ld, int64_t prows, int64_t pcols, hipStream_t s);
 // Batched classical product on the fp64 matrix cores: C_b = A_b * B_b, all m x m.

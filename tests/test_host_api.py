@@ -105,12 +105,16 @@ def test_plan_memory_with_peeling_at_every_level():
         return (ld * h + 31) // 32 * 32
     sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
     try:
-        # extents halve rounding down: 1001 -> 500 -> 250 -> 125; no copies, nothing for the peeled parts
-        assert sw.sw_plan_memory(1001, 3, "DDD") == (2 * elems(500) + 2 * elems(250) + 2 * elems(125)) * 8
+        # extents halve rounding down: 1001 -> 500 -> 250 -> 125; no copies of the operands; a level with an odd inner
+        # extent sets the peeled column of A and row of B aside (each rounded up to 32 doubles per problem)
+        def side(e):
+            return 2 * ((e + 31) // 32 * 32)
+        assert sw.sw_plan_memory(1001, 3, "DDD") == (side(1000) + 2 * elems(500) + 2 * elems(250) + 2 * elems(125)) * 8
+        assert sw.sw_plan_memory(1000, 3, "DDD") == (2 * elems(500) + 2 * elems(250) + 2 * elems(125)) * 8
         # a pair of BFS steps is one pass only where the level between them is even: 1001 -> 500 (even) fuses ...
-        assert sw.sw_plan_memory(1001, 2, "BB") == 3 * 49 * elems(250) * 8
-        # ... 1003 -> 501 (odd) does not: seven children of 501, then their 49 of 250
-        assert sw.sw_plan_memory(1003, 2, "BB") == (21 * elems(501) + 21 * 7 * elems(250)) * 8
+        assert sw.sw_plan_memory(1001, 2, "BB") == (side(1000) + 3 * 49 * elems(250)) * 8
+        # ... 1003 -> 501 (odd) does not: seven children of 501, each peeled again, then their 49 of 250
+        assert sw.sw_plan_memory(1003, 2, "BB") == (side(1002) + 21 * elems(501) + 7 * side(500) + 21 * 7 * elems(250)) * 8
         assert sw.sw_plan_schedule(94097, 5, (290 << 30) - 3 * 94097 ** 2 * 8) == "DDDBB"
         with pytest.raises(sw.SwError):
             sw.sw_plan_memory(7, 3, "DDD")
