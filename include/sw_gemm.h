@@ -245,7 +245,9 @@ int sw_set_overlap(int on);
  * the recursion is odd, the last row, column and inner index are peeled off there, the step runs on the even
  * part and the peeled parts are finished by thin classical products (C11 += a12*b21, c12 = [A11 a12]*[b12;b22],
  * [c21 c22] = [a21 a22]*B) for all problems of that level at once; the children may be odd again.  Needs only
- * 2^levels <= n.  Two BFS steps are fused only where the level between them is even. */
+ * 2^levels <= n.  Two BFS steps are fused only where the level between them is even.  Workspace: what the halved
+ * (rounded-down) extents need, plus a copy of the peeled column of A and row of B per problem of a level whose
+ * inner extent is odd (sw_plan_memory counts it). */
 #define SW_ODD_PEEL_LEVELS 2
 int sw_set_odd_mode(int mode);
 const char* sw_last_error(void);                    /* HOST string, valid until the thread's next call  */
