@@ -286,7 +286,8 @@ def test_peeling_at_every_odd_level_matches_oracle(oracle, n, levels):
 def test_peeling_at_every_odd_level_on_rectangular_products():
     sw.sw_set_odd_mode(sw.SW_ODD_PEEL_LEVELS)
     try:
-        for (M, N, K, levels, order) in [(301, 515, 777, 3, "DBD"), (1001, 64, 333, 2, "BB"), (97, 97, 1030, 4, "DDBB"), (640, 641, 642, 3, "BDB")]:
+        for (M, N, K, levels, order) in [(301, 515, 777, 3, "DBD"), (1001, 64, 333, 2, "BB"), (97, 97, 1030, 4, "DDBB"), (640, 641, 642, 3, "BDB"),
+                                     (65, 131, 4099, 1, "B"), (4101, 35, 67, 1, "D"), (35, 4611, 2049, 2, "BB")]:   # one-wide kernels: several LDS chunks of the inner index, many row and column blocks
             g = torch.Generator(device=DEV).manual_seed(M + N)
             A = torch.randint(-8, 9, (M, K), generator=g, device=DEV, dtype=torch.int32).to(torch.float64)
             B = torch.randint(-8, 9, (K, N), generator=g, device=DEV, dtype=torch.int32).to(torch.float64)
