@@ -84,6 +84,26 @@ __global__ void __launch_bounds__(64) meter_kernel(int64_t* out, int iters)
     if (threadIdx.x == 0) { out[0] = c0; out[1] = c1; out[2] = w0; out[3] = w1; }
 }
 
+// The matrix pipes alone: every wavefront issues `iters` rounds of 16 independent v_mfma_f64_16x16x4_f64 on operands
+// held in registers (the accumulator tile of the leaf kernel, 4 x 4 MFMA tiles, without its loads).  Two workgroups of
+// four wavefronts per CU, as the leaf kernel runs.  2 * 16 * 16 * 4 = 2048 flops per instruction and wavefront.
+typedef double v4d __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256, 2) mfma_kernel(double* __restrict__ out, int iters, double a0, double b0)
+{
+    v4d acc[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) acc[t] = (v4d){0.0, 0.0, 0.0, 0.0};
+    const double a = a0 + 1e-9 * (double)(threadIdx.x & 63), b = b0;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[t], 0, 0, 0);
+    }
+    v4d s = acc[0];
+#pragma unroll
+    for (int t = 1; t < 16; ++t) s += acc[t];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = (s[0] + s[1]) + (s[2] + s[3]);
+}
+
 }  // namespace
 
 // n2: elements of 16 bytes per stream; chunks: 1, or 4 for (1, 8), (4, 7), (7, 4) and (16, 49) streams;
@@ -122,5 +142,13 @@ extern "C" int sw_probe_meter(void* out, int iters, void* hip_stream)
 {
     if (iters < 0) return -1;
     hipLaunchKernelGGL(meter_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (int64_t*)out, iters);
+    return (int)hipGetLastError();
+}
+
+// The matrix-pipe probe (see mfma_kernel): out holds blocks * 256 doubles.  Returns 0, -1, or the HIP error code.
+extern "C" int sw_probe_mfma(void* out, int blocks, int iters, void* hip_stream)
+{
+    if (blocks < 1 || iters < 0) return -1;
+    hipLaunchKernelGGL(mfma_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, (double*)out, iters, 1.0, 0.5);
     return (int)hipGetLastError();
 }

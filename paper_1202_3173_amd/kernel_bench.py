@@ -17,6 +17,7 @@
                                                                             # output streams: what HBM sustains
   python -m paper_1202_3173_amd.kernel_bench beside --m 2940 --batch 49       # leaf products next to background
                                                                             # traffic, with the shader clock
+  python -m paper_1202_3173_amd.kernel_bench mfma                             # the fp64 matrix pipes on registers alone
   python -m paper_1202_3173_amd.kernel_bench error_growth --n 2048           # error against the depth, with and
                                                                             # without diagonal scaling (Section 6.1)
 
@@ -236,6 +237,39 @@ def beside_study(m, batch, launches):
         print(f"| {label} | {rate} | {mid:.3f} | {flops / mid / 1e9:.1f} | {flops / mid / 1e9 / FP64_MFMA_PEAK_TFLOPS:.3f} | {mhz:.0f} |", flush=True)
 
 
+def mfma_peak(iters):
+    """What the fp64 matrix pipes sustain without any memory traffic: 512 workgroups (two per CU) of four wavefronts,
+    each issuing rounds of 16 independent v_mfma_f64_16x16x4_f64 on registers; the shader clock is read beside it."""
+    import ctypes
+    import os
+    import torch
+    X = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsw_probe.so"))
+    X.sw_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    X.sw_probe_meter.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    blocks, rounds = 512, 200000
+    out = torch.empty(blocks * 256, dtype=torch.float64, device=dev)
+    stamps = torch.zeros(4, dtype=torch.int64, device=dev)
+    s_meter = torch.cuda.Stream()
+    st = torch.cuda.current_stream().cuda_stream
+    flops = blocks * 4 * rounds * 16 * 2048.0
+
+    def launch():
+        assert X.sw_probe_mfma(out.data_ptr(), blocks, rounds, st) == 0
+    _timed(launch, 2, 1)                                          # bring the clock up
+    expect_ms = flops / 75e12 * 1e3
+    assert X.sw_probe_meter(stamps.data_ptr(), int(0.75 * iters * expect_ms * 1e3 / 3.5), s_meter.cuda_stream) == 0
+    ms = _timed(launch, iters, 0)
+    torch.cuda.synchronize()
+    t = stamps.cpu().tolist()
+    mhz = (t[1] - t[0]) / ((t[3] - t[2]) / 100.0)
+    rate = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({"kernel": "mfma_f64_16x16x4 on registers", "workgroups": blocks, "avg_ms": round(ms, 3), "TFLOPs": round(rate, 2),
+                      "frac_of_fp64_mfma_peak": round(rate / FP64_MFMA_PEAK_TFLOPS, 4), "shader_clock_MHz": round(mhz),
+                      "TFLOPs_at_2400_MHz": round(rate * 2400.0 / mhz, 2)}))
+
+
 def error_growth(n):
     """Markdown tables: the largest entry-wise error relative to ||A(i,:)|| ||B(:,j)|| (the quantity the scaled bound
     of Section 6.1 is stated in) in units of n*eps, and in brackets the norm-wise error in units of
@@ -281,7 +315,7 @@ def error_growth(n):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "pre_add2", "post_add2", "copy", "dgemm", "depth", "orders", "streams", "beside", "error_growth"])
+    ap.add_argument("kernel", choices=["leaf", "pre_add", "post_add", "pre_add2", "post_add2", "copy", "dgemm", "depth", "orders", "streams", "beside", "mfma", "error_growth"])
     ap.add_argument("--sizes", default="2048,4096,8192,16384,23520,32768,47040", help="depth: the sizes n")
     ap.add_argument("--max-levels", type=int, default=6, help="depth: the largest depth tried")
     ap.add_argument("--n", type=int, default=2048, help="orders, error_growth: the size n")
@@ -316,6 +350,8 @@ def main():
         return stream_sweep(args.bytes, args.iters)
     if args.kernel == "beside":
         return beside_study(args.m, args.batch, args.iters)
+    if args.kernel == "mfma":
+        return mfma_peak(args.iters)
 
     import torch
     from paper_1202_3173_amd import binding as sw
